@@ -1,0 +1,185 @@
+/*
+ * hcnn.h -- C ABI of the MI355X (gfx950) library for the hot path of HCNN's
+ * encrypted CNN inference: RNS-form FV/BFV ciphertext arithmetic.
+ *
+ * Citations name sections, tables and equations of the HCNN paper
+ * (arXiv 1811.00778).
+ *
+ * Data model (Sec. 2.1): R = Z[X]/(X^n+1), ciphertext modulus q = q_0*...*q_{k-1}
+ * (distinct primes, 2^29 < q_i < 2^30, q_i = 1 mod 2n), plaintext modulus t (prime,
+ * t = 1 mod 2n for slot packing, Sec. 4.2 end).  A polynomial of R_q is stored as
+ * k rows of n uint32 residues ("limb-major"): row l holds the coefficients mod q_l,
+ * canonical in [0, q_l).  A ciphertext is uint32[2][k][n]; a batch is
+ * uint32[n_ct][2][k][n].  Unless an entry point says otherwise, ciphertexts cross
+ * this boundary in the coefficient domain.
+ *
+ * Pointers named *_dev are DEVICE pointers (HBM), 16-byte aligned, owned by the
+ * caller; *_host are host pointers.  Input and output buffers must not overlap
+ * unless "in place" is stated.  The library owns the context, its tables and its
+ * scratch memory.  Every call enqueues work on the context's HIP stream and
+ * returns without synchronising (hcnn_get_stat synchronises).  Return value: 0 on
+ * success, a negative HCNN_ERR_* code for rejected arguments (nothing was
+ * enqueued), or a positive hipError_t value when the HIP runtime failed.  No
+ * exception or abort crosses this boundary.  No randomness is drawn inside the
+ * library: every random polynomial is an argument.
+ *
+ * Conventions the paper leaves open:
+ *   - psi_l, the primitive 2n-th root of unity mod q_l used by the transforms, is
+ *     x^((q_l-1)/2n) for the smallest x >= 2 for which that power has order 2n;
+ *   - NTT-domain index j holds the value of the polynomial at psi_l^(2*brev(j)+1),
+ *     brev = bit reversal on log2(n) bits;
+ *   - before the tensor product residues are lifted to the centred interval
+ *     [-(q-1)/2, (q-1)/2];
+ *   - relinearisation digits are the RNS residues: digit i of c2 is the polynomial
+ *     with coefficients (c2 mod q_i) in [0, q_i), and evaluation-key component i
+ *     encrypts g_i*s^2 with g_i = (q/q_i)*((q/q_i)^-1 mod q_i).
+ */
+#ifndef HCNN_H
+#define HCNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hcnn_ctx hcnn_ctx;
+
+enum {
+  HCNN_OK = 0,
+  HCNN_ERR_NULL = -1,     /* a required pointer is null                                     */
+  HCNN_ERR_N = -2,        /* n is not a power of two in [2^10, 2^15]                        */
+  HCNN_ERR_PRIME = -3,    /* a modulus is not a prime in (2^29, 2^30), not 1 mod 2n, or repeated */
+  HCNN_ERR_T = -4,        /* t is not a prime below 2^29, or equals a ciphertext prime      */
+  HCNN_ERR_AUX = -5,      /* auxiliary basis too small: needs p_0*...*p_{k'-1} > t*n*q + 1    */
+  HCNN_ERR_ARG = -6,      /* a count or size is zero, too large, or inconsistent            */
+  HCNN_ERR_NOKEY = -7,    /* hcnn_ct_square_relin before hcnn_set_relin_key                 */
+  HCNN_ERR_ALIGN = -8,    /* a device pointer is not 16-byte aligned                        */
+  HCNN_ERR_NODEVICE = -9  /* no usable gfx950 device / LDS too small for this n             */
+};
+
+/* Limits. */
+#define HCNN_MAX_LIMBS 32u        /* k <= 32 and k' <= 32 */
+#define HCNN_MAX_FILTERS 16u      /* F of hcnn_ct_scalar_mac */
+
+/* ---- parameter helpers (host only, no device needed) ------------------------------- */
+
+/* Writes to primes_host[0..count) the `count` largest primes below 2^30 that are
+ * 1 mod 2n, in descending order.  The usual choice is: the first k are q_0..q_{k-1},
+ * the next k' the auxiliary basis. */
+int hcnn_gen_primes(uint32_t n, uint32_t count, uint32_t* primes_host);
+
+/* Smallest k' such that candidates_host[0..k') (distinct primes as above, none among
+ * q) has product > t*n*q + 1: the range needed to hold the scaled tensor product
+ * round(t*c*c'/q) of Sec. 2.1 (HMult step 2) exactly.  HCNN_ERR_AUX if n_candidates
+ * do not suffice. */
+int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q_primes_host, uint32_t t,
+                       const uint32_t* candidates_host, uint32_t n_candidates, uint32_t* k_aux_out);
+
+/* ---- context ------------------------------------------------------------------------ */
+
+/* Builds all tables (roots of unity, base-conversion constants) for ring degree n,
+ * ciphertext primes q_primes_host[0..k), auxiliary primes p_primes_host[0..k_aux) and
+ * plaintext modulus t, uploads them to the current HIP device and binds the context
+ * to hip_stream (a hipStream_t passed as void*; NULL = the default stream).
+ * k_aux may be 0 when hcnn_ct_square_relin is not used. */
+int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q_primes_host,
+                    uint32_t k_aux, const uint32_t* p_primes_host, uint32_t t, void* hip_stream);
+int hcnn_ctx_destroy(hcnn_ctx* ctx);
+int hcnn_set_stream(hcnn_ctx* ctx, void* hip_stream);
+
+/* Evaluation key of Sec. 2.1 (KeyGen), one component per RNS prime:
+ * evk_dev = uint32[k][2][k][n], evk[i][0] = g_i*s^2 - (a_i*s + e_i), evk[i][1] = a_i,
+ * coefficient domain.  The library keeps its own NTT-domain copy; the caller's
+ * buffer is free again once the stream has passed this call. */
+int hcnn_set_relin_key(hcnn_ctx* ctx, const uint32_t* evk_dev);
+
+/* ---- hot path ----------------------------------------------------------------------- */
+
+/* Batched negacyclic number-theoretic transform, in place, on n_polys polynomials:
+ * polys_dev = uint32[n_polys][k][n].  Forward: row l becomes the values at
+ * psi_l^(2*brev(j)+1), j = 0..n-1 -- the CRT decomposition of Sec. 2.1.1 applied to a
+ * ciphertext prime; products in R_q (Sec. 2.1) become slot-wise products.  Inverse:
+ * the exact inverse map (includes the factor n^-1).  Residues in and out are canonical. */
+int hcnn_ntt_fwd(hcnn_ctx* ctx, uint32_t* polys_dev, size_t n_polys);
+int hcnn_ntt_inv(hcnn_ctx* ctx, uint32_t* polys_dev, size_t n_polys);
+
+/* Convolution-type layer (Sec. 3.2 "Convolution-Type Layers", Sec. 4.3): every output
+ * node is sum_tau w_tau * z_tau over ciphertexts, i.e. HMultPlain by the constant
+ * integer w_tau (same weight in every slot) followed by HAdd; no bias.
+ *   in_cts_dev  uint32[n_in][2][k][n]
+ *   idx_dev     uint32[n_grp][T]      input ciphertext index of term tau of group g
+ *   w_dev       int32 [n_grp][F][T]   signed integer weights
+ *   out_cts_dev uint32[F][n_grp][2][k][n]
+ *   out[f][g] = sum_{tau<T} w[g][f][tau] * in[idx[g][tau]]   (mod q, both polynomials)
+ * F outputs share one gather row: F = number of filters of a convolution (g runs over
+ * the filter placements f_jk = j*s_h*i_w + k*s_w of Sec. 4.4.1) or the number of
+ * outputs of a fully connected layer (n_grp = 1); F = 1 gives independent rows.
+ * w_abs_max >= 0 is the caller's bound on |w| (it sets how often partial sums are reduced).
+ * Works in either domain (the map is linear) as long as in and out use the same one.
+ * An index >= n_in or a weight beyond the bound is skipped and counted in
+ * HCNN_STAT_BAD_INPUT; the outputs touched are then unspecified.
+ * 1 <= F <= HCNN_MAX_FILTERS. */
+int hcnn_ct_scalar_mac(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_in,
+                       const uint32_t* idx_dev, const int32_t* w_dev, int32_t w_abs_max,
+                       size_t n_grp, size_t F, size_t T, uint32_t* out_cts_dev);
+
+/* Square activation (Sec. 3.2, "Square layer"; HSquare of Table "FHE primitives
+ * benchmarks") on n_ct ciphertexts: HMult(c, c) of Sec. 2.1 --
+ *   tensor (c0*c0, 2*c0*c1, c1*c1) over the integers on centred lifts,
+ *   scaling round(t/q * .) of each coefficient (exact; ties cannot occur),
+ *   relinearisation c'_b = y_b + sum_i evk[i][b] * digit_i(y_2) in R_q.
+ * in_cts_dev, out_cts_dev = uint32[n_ct][2][k][n]; may be the same buffer (in place).
+ * Needs k_aux auxiliary primes and hcnn_set_relin_key. */
+int hcnn_ct_square_relin(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_ct,
+                         uint32_t* out_cts_dev);
+
+/* ---- test helpers (same kernels, not tuned) ------------------------------------------- */
+
+/* KeyGen of Sec. 2.1 with the randomness passed in:
+ *   s_dev int32[n] (secret, small), a_dev uint32[k][n], e_dev int32[n],
+ *   a_evk_dev uint32[k][k][n] (a_i of component i), e_evk_dev int32[k][n];
+ *   pk_out_dev uint32[2][k][n] = (e - a*s, a);  evk_out_dev uint32[k][2][k][n] as in
+ *   hcnn_set_relin_key.  evk_out_dev may be NULL (public key only). */
+int hcnn_keygen(hcnn_ctx* ctx, const int32_t* s_dev, const uint32_t* a_dev, const int32_t* e_dev,
+                const uint32_t* a_evk_dev, const int32_t* e_evk_dev,
+                uint32_t* pk_out_dev, uint32_t* evk_out_dev);
+
+/* Encrypt of Sec. 2.1: c = (pk0*u + e1 + floor(q/t)*m, pk1*u + e2).
+ *   pk_dev uint32[2][k][n]; m_dev uint32[n_ct][n] with entries in [0,t);
+ *   u_dev, e1_dev, e2_dev int32[n_ct][n] (small); ct_out_dev uint32[n_ct][2][k][n]. */
+int hcnn_encrypt(hcnn_ctx* ctx, const uint32_t* pk_dev, const uint32_t* m_dev, const int32_t* u_dev,
+                 const int32_t* e1_dev, const int32_t* e2_dev, size_t n_ct, uint32_t* ct_out_dev);
+
+/* Decrypt of Sec. 2.1: m = round(t/q * (c0 + c1*s mod q)) mod t, exact.
+ *   sk_dev int32[n]; ct_dev uint32[n_ct][2][k][n]; m_out_dev uint32[n_ct][n]. */
+int hcnn_decrypt(hcnn_ctx* ctx, const int32_t* sk_dev, const uint32_t* ct_dev, size_t n_ct,
+                 uint32_t* m_out_dev);
+
+/* ---- diagnostics ---------------------------------------------------------------------- */
+enum {
+  HCNN_STAT_EXACT_FALLBACKS = 0, /* coefficients whose base conversion needed the exact
+                                    mixed-radix comparison instead of the fixed-point estimate */
+  HCNN_STAT_BAD_INPUT = 1,       /* out-of-range indices / weights seen by hcnn_ct_scalar_mac   */
+  HCNN_STAT_SCRATCH_BYTES = 2    /* device scratch currently held by the context               */
+};
+/* Synchronises the context's stream, then reads the counter. */
+int hcnn_get_stat(hcnn_ctx* ctx, int which, uint64_t* out);
+int hcnn_reset_stats(hcnn_ctx* ctx);
+
+enum {
+  HCNN_OPT_AMBIGUITY_BAND = 0,  /* width (in units of 2^-64 of the modulus) of the band around
+                                   the rounding boundary inside which the exact comparison is
+                                   used; default 256; raising it only costs time (for tests) */
+  HCNN_OPT_SQUARE_CHUNK = 1     /* ciphertexts per internal batch of hcnn_ct_square_relin;
+                                   0 = choose from the scratch budget */
+};
+int hcnn_set_option(hcnn_ctx* ctx, int which, uint64_t value);
+
+const char* hcnn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCNN_H */

@@ -1,0 +1,140 @@
+"""Entry points of include/hcnn.h as methods; array handling is supplied by a subclass.
+
+A subclass provides
+    _ptr(x)                      integer address of array x (device memory in the product)
+    _empty(shape, dtype_name)    new uninitialised array ("u32" or "i32")
+    _check(x, dtype_name)        raises unless x is a contiguous array of that type
+Marshalling only: no arithmetic of the method happens here.
+"""
+from . import _capi
+
+
+class OpsMixin:
+    raw: _capi.RawContext
+
+    def close(self):
+        self.raw.close()
+
+    # ---- shapes
+    @property
+    def n(self):
+        return self.raw.n
+
+    @property
+    def k(self):
+        return self.raw.k
+
+    @property
+    def ct_shape(self):
+        return (2, self.raw.k, self.raw.n)
+
+    # ---- hot path
+    def ntt_fwd(self, polys):
+        """In-place forward negacyclic NTT of polys [n_polys][k][n] (hcnn_ntt_fwd)."""
+        self._check(polys, "u32")
+        self.raw.call("hcnn_ntt_fwd", self._ptr(polys), self._count(polys, (self.k, self.n)))
+        return polys
+
+    def ntt_inv(self, polys):
+        """In-place inverse negacyclic NTT (hcnn_ntt_inv)."""
+        self._check(polys, "u32")
+        self.raw.call("hcnn_ntt_inv", self._ptr(polys), self._count(polys, (self.k, self.n)))
+        return polys
+
+    def ct_scalar_mac(self, in_cts, idx, w, w_abs_max, out=None):
+        """out[f][g] = sum_tau w[g][f][tau] * in[idx[g][tau]] (hcnn_ct_scalar_mac).
+        in_cts [n_in][2][k][n]; idx [G][T] u32; w [G][F][T] i32; returns [F][G][2][k][n]."""
+        self._check(in_cts, "u32"); self._check(idx, "u32"); self._check(w, "i32")
+        n_in = self._count(in_cts, self.ct_shape)
+        G, T = tuple(idx.shape)
+        Gw, F, Tw = tuple(w.shape)
+        if (Gw, Tw) != (G, T):
+            raise ValueError("w must be [G][F][T] matching idx [G][T]")
+        if out is None:
+            out = self._empty((F, G) + self.ct_shape, "u32")
+        self._check(out, "u32")
+        if tuple(out.shape) != (F, G) + self.ct_shape:
+            raise ValueError("out must be [F][G][2][k][n]")
+        self.raw.call("hcnn_ct_scalar_mac", self._ptr(in_cts), n_in, self._ptr(idx), self._ptr(w),
+                      int(w_abs_max), G, F, T, self._ptr(out))
+        return out
+
+    def set_relin_key(self, evk):
+        self._check(evk, "u32")
+        if tuple(evk.shape) != (self.k, 2, self.k, self.n):
+            raise ValueError("evk must be [k][2][k][n]")
+        self.raw.call("hcnn_set_relin_key", self._ptr(evk))
+
+    def ct_square_relin(self, in_cts, out=None):
+        """Square + scale + relinearise every ciphertext of in_cts [n_ct][2][k][n] (hcnn_ct_square_relin)."""
+        self._check(in_cts, "u32")
+        n_ct = self._count(in_cts, self.ct_shape)
+        if out is None:
+            out = self._empty(tuple(in_cts.shape), "u32")
+        self._check(out, "u32")
+        if tuple(out.shape) != tuple(in_cts.shape):
+            raise ValueError("out must have the shape of in_cts")
+        self.raw.call("hcnn_ct_square_relin", self._ptr(in_cts), n_ct, self._ptr(out))
+        return out
+
+    # ---- test helpers
+    def keygen(self, s, a, e, a_evk=None, e_evk=None):
+        self._check(s, "i32"); self._check(a, "u32"); self._check(e, "i32")
+        pk = self._empty(self.ct_shape, "u32")
+        evk = None
+        if a_evk is not None:
+            self._check(a_evk, "u32"); self._check(e_evk, "i32")
+            evk = self._empty((self.k, 2, self.k, self.n), "u32")
+        self.raw.call("hcnn_keygen", self._ptr(s), self._ptr(a), self._ptr(e),
+                      self._ptr(a_evk) if a_evk is not None else None,
+                      self._ptr(e_evk) if e_evk is not None else None,
+                      self._ptr(pk), self._ptr(evk) if evk is not None else None)
+        return pk, evk
+
+    def encrypt(self, pk, m, u, e1, e2):
+        """m [n_ct][n] u32 in [0,t); u, e1, e2 [n_ct][n] i32 -> [n_ct][2][k][n] (hcnn_encrypt)."""
+        for x, d in ((pk, "u32"), (m, "u32"), (u, "i32"), (e1, "i32"), (e2, "i32")):
+            self._check(x, d)
+        n_ct = self._count(m, (self.n,))
+        out = self._empty((n_ct,) + self.ct_shape, "u32")
+        self.raw.call("hcnn_encrypt", self._ptr(pk), self._ptr(m), self._ptr(u), self._ptr(e1), self._ptr(e2),
+                      n_ct, self._ptr(out))
+        return out
+
+    def decrypt(self, sk, cts):
+        self._check(sk, "i32"); self._check(cts, "u32")
+        n_ct = self._count(cts, self.ct_shape)
+        out = self._empty((n_ct, self.n), "u32")
+        self.raw.call("hcnn_decrypt", self._ptr(sk), self._ptr(cts), n_ct, self._ptr(out))
+        return out
+
+    # ---- diagnostics
+    def exact_fallbacks(self):
+        return self.raw.stat(_capi.STAT_EXACT_FALLBACKS)
+
+    def bad_inputs(self):
+        return self.raw.stat(_capi.STAT_BAD_INPUT)
+
+    def scratch_bytes(self):
+        return self.raw.stat(_capi.STAT_SCRATCH_BYTES)
+
+    def reset_stats(self):
+        self.raw.call("hcnn_reset_stats")
+
+    def set_ambiguity_band(self, band):
+        self.raw.set_option(_capi.OPT_AMBIGUITY_BAND, band)
+
+    def set_square_chunk(self, chunk):
+        self.raw.set_option(_capi.OPT_SQUARE_CHUNK, chunk)
+
+    # ---- helpers
+    @staticmethod
+    def _count(x, tail):
+        shape = tuple(x.shape)
+        tail = tuple(tail)
+        if len(shape) < len(tail) or shape[len(shape) - len(tail):] != tail:
+            raise ValueError("expected trailing shape %r, got %r" % (tail, shape))
+        cnt = 1
+        for d in shape[:len(shape) - len(tail)]:
+            cnt *= int(d)
+        return cnt

@@ -1,0 +1,801 @@
+// C ABI, context, table generation and kernel orchestration.
+// Compiled as HIP for gfx950 (the product) or, with -DHCNN_HOSTEMU, as plain C++
+// for the CPU checker of the kernel sources.
+#include "../../include/hcnn.h"
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "fv_kernels.h"
+#include "ntt_kernels.h"
+
+using namespace hcnn;
+
+namespace {
+
+typedef unsigned __int128 u128;
+
+// ---------------------------------------------------------------- host number theory
+uint32_t h_mulmod(uint32_t a, uint32_t b, uint32_t m) { return (uint32_t)(((uint64_t)a * b) % m); }
+uint32_t h_powmod(uint32_t a, uint64_t e, uint32_t m) {
+  uint64_t r = 1, b = a % m;
+  while (e) {
+    if (e & 1) r = r * b % m;
+    b = b * b % m;
+    e >>= 1;
+  }
+  return (uint32_t)r;
+}
+uint32_t h_inv(uint32_t a, uint32_t prime) { return h_powmod(a % prime, (uint64_t)prime - 2, prime); }
+
+bool h_is_prime(uint32_t x) {
+  if (x < 2) return false;
+  for (uint32_t sp : {2u, 3u, 5u, 7u, 11u, 13u}) {
+    if (x % sp == 0) return x == sp;
+  }
+  uint32_t d = x - 1;
+  int r = 0;
+  while ((d & 1) == 0) { d >>= 1; ++r; }
+  for (uint32_t a : {2u, 3u, 5u, 7u}) {          // decides every x < 3,215,031,751
+    uint64_t y = h_powmod(a, d, x);
+    if (y == 1 || y == x - 1) continue;
+    bool comp = true;
+    for (int i = 1; i < r; ++i) {
+      y = y * y % x;
+      if (y == x - 1) { comp = false; break; }
+    }
+    if (comp) return false;
+  }
+  return true;
+}
+
+// psi = x^((p-1)/2n) for the smallest x >= 2 giving order exactly 2n
+uint32_t h_root_of_unity(uint32_t n, uint32_t p) {
+  const uint64_t e = ((uint64_t)p - 1) / (2ull * n);
+  for (uint32_t x = 2;; ++x) {
+    uint32_t psi = h_powmod(x, e, p);
+    if (h_powmod(psi, n, p) == p - 1) return psi;
+  }
+}
+
+uint32_t h_brev(uint32_t v, int bits) {
+  uint32_t r = 0;
+  for (int i = 0; i < bits; ++i) { r = (r << 1) | (v & 1); v >>= 1; }
+  return r;
+}
+
+ShoupConst h_shoup(uint32_t w, uint32_t p) {
+  ShoupConst c;
+  c.w = w;
+  c.ws = (uint32_t)(((uint64_t)w << 32) / p);
+  return c;
+}
+
+Mod h_mod(uint32_t p) {
+  Mod m;
+  m.p = p;
+  m.c32 = (uint32_t)((1ull << 32) % p);
+  m.c32s = (uint32_t)(((uint64_t)m.c32 << 32) / p);
+  m.mu = (uint32_t)((1ull << 61) / p);
+  return m;
+}
+
+// product of all `ms` except index `skip` (skip < 0: all), modulo m
+uint32_t h_prod_mod(const std::vector<uint32_t>& ms, int skip, uint32_t m) {
+  uint64_t r = 1 % m;
+  for (int i = 0; i < (int)ms.size(); ++i)
+    if (i != skip) r = r * (ms[i] % m) % m;
+  return (uint32_t)r;
+}
+
+// little-endian multiword natural numbers, only for the size check of the auxiliary basis
+typedef std::vector<uint32_t> Big;
+void big_mul_small(Big& a, uint32_t f) {
+  uint64_t carry = 0;
+  for (auto& w : a) {
+    uint64_t t = (uint64_t)w * f + carry;
+    w = (uint32_t)t;
+    carry = t >> 32;
+  }
+  if (carry) a.push_back((uint32_t)carry);
+}
+void big_add_small(Big& a, uint32_t v) {
+  uint64_t carry = v;
+  for (auto& w : a) {
+    uint64_t t = (uint64_t)w + carry;
+    w = (uint32_t)t;
+    carry = t >> 32;
+    if (!carry) break;
+  }
+  if (carry) a.push_back((uint32_t)carry);
+}
+int big_cmp(Big a, Big b) {
+  while (!a.empty() && a.back() == 0) a.pop_back();
+  while (!b.empty() && b.back() == 0) b.pop_back();
+  if (a.size() != b.size()) return a.size() < b.size() ? -1 : 1;
+  for (size_t i = a.size(); i-- > 0;)
+    if (a[i] != b[i]) return a[i] < b[i] ? -1 : 1;
+  return 0;
+}
+
+bool valid_n(uint32_t n) { return n >= 1024 && n <= 32768 && (n & (n - 1)) == 0; }
+bool valid_rns_prime(uint32_t p, uint32_t n) {
+  return p > (1u << 29) && p < (1u << 30) && (p - 1) % (2 * n) == 0 && h_is_prime(p);
+}
+
+int check_primes(uint32_t n, const uint32_t* q, uint32_t k, const uint32_t* p, uint32_t kp) {
+  std::vector<uint32_t> all(q, q + k);
+  if (kp) all.insert(all.end(), p, p + kp);
+  for (uint32_t v : all)
+    if (!valid_rns_prime(v, n)) return HCNN_ERR_PRIME;
+  std::sort(all.begin(), all.end());
+  if (std::adjacent_find(all.begin(), all.end()) != all.end()) return HCNN_ERR_PRIME;
+  return HCNN_OK;
+}
+
+// is prod(p[0..kp)) > t*n*prod(q) + 1 ?
+bool aux_sufficient(uint32_t n, const uint32_t* q, uint32_t k, uint32_t t, const uint32_t* p, uint32_t kp) {
+  Big lhs{1}, rhs{1};
+  for (uint32_t j = 0; j < kp; ++j) big_mul_small(lhs, p[j]);
+  for (uint32_t i = 0; i < k; ++i) big_mul_small(rhs, q[i]);
+  big_mul_small(rhs, t);
+  big_mul_small(rhs, n);
+  big_add_small(rhs, 1);
+  return big_cmp(lhs, rhs) > 0;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+// ---------------------------------------------------------------- context
+struct BConvHost {
+  uint32_t ks = 0, kd = 0;
+  std::vector<Mod> src_mod, dst_mod;
+  std::vector<ShoupConst> zmul, xmul;
+  std::vector<uint64_t> fix;
+  std::vector<uint32_t> ginv, half, B, Mmod;
+};
+
+struct hcnn_ctx {
+  uint32_t n = 0, logn = 0, k = 0, kp = 0, t = 0;
+  std::vector<uint32_t> q, p;
+  hcnn_stream_t stream = nullptr;
+  std::vector<void*> owned;
+
+  Mod* d_mods = nullptr;            // [k + kp]
+  NttLimb* d_limbs = nullptr;       // [k + kp]
+  ShoupConst* d_tw_fwd = nullptr;   // [k + kp][n]
+  ShoupConst* d_tw_inv = nullptr;
+  ShoupConst* d_delta = nullptr;    // [k] floor(q/t) mod q_l
+  ShoupConst* d_tq_inv = nullptr;   // [kp]
+  BConvDev ext{}, to_p{}, to_q{}, dec{};
+  uint32_t neg_qinv_t = 0;
+  unsigned long long* d_counters = nullptr;   // [2]
+
+  uint32_t* d_evk_hat = nullptr;
+  bool has_key = false;
+
+  uint32_t* scratch = nullptr;
+  size_t scratch_bytes = 0;
+
+  uint64_t band = 256;
+  uint64_t square_chunk = 0;
+  size_t max_lds = 0;
+};
+
+namespace {
+
+template <class T>
+int upload(hcnn_ctx* c, const std::vector<T>& h, T** d) {
+  void* ptr = nullptr;
+  int e = dev_malloc(&ptr, h.size() * sizeof(T));
+  if (e) return e;
+  c->owned.push_back(ptr);
+  if (!h.empty()) {
+    e = copy_h2d(ptr, h.data(), h.size() * sizeof(T), c->stream);
+    if (e) return e;
+  }
+  *d = (T*)ptr;
+  return 0;
+}
+
+// Tables of an exact centred base conversion src -> dst.
+//   zfac[i]   extra factor folded into z_i (1 or t), also used as xmul
+//   fold_inv  when true, B and Mmod carry the factor M^-1 (B = m_i^-1 mod m'_j, Mmod = 1)
+BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_t>& dst, uint32_t zfac,
+                     bool fold_inv, bool dst_is_rns_prime) {
+  BConvHost h;
+  h.ks = (uint32_t)src.size();
+  h.kd = (uint32_t)dst.size();
+  for (uint32_t i = 0; i < h.ks; ++i) {
+    const uint32_t m = src[i];
+    h.src_mod.push_back(h_mod(m));
+    const uint32_t Mi_inv = h_inv(h_prod_mod(src, (int)i, m), m);        // (M/m_i)^-1 mod m_i
+    h.zmul.push_back(h_shoup(h_mulmod(Mi_inv, zfac % m, m), m));
+    h.xmul.push_back(h_shoup(zfac % m, m));
+    h.fix.push_back((uint64_t)((((u128)1) << 93) / m));
+  }
+  h.ginv.assign((size_t)h.ks * h.ks, 0);
+  for (uint32_t i = 0; i < h.ks; ++i)
+    for (uint32_t l = 0; l < i; ++l) h.ginv[(size_t)i * h.ks + l] = h_inv(src[l] % src[i], src[i]);
+  // mixed-radix digits of (M-1)/2, whose residue mod m_i is (m_i-1)/2
+  h.half.assign(h.ks, 0);
+  for (uint32_t i = 0; i < h.ks; ++i) {
+    uint32_t tt = (src[i] - 1) / 2;
+    for (uint32_t l = 0; l < i; ++l) {
+      uint32_t al = h.half[l] % src[i];
+      tt = (tt + src[i] - al) % src[i];
+      tt = h_mulmod(tt, h.ginv[(size_t)i * h.ks + l], src[i]);
+    }
+    h.half[i] = tt;
+  }
+  h.B.assign((size_t)h.ks * h.kd, 0);
+  h.Mmod.assign(h.kd, 0);
+  for (uint32_t j = 0; j < h.kd; ++j) {
+    const uint32_t mj = dst[j];
+    if (dst_is_rns_prime) h.dst_mod.push_back(h_mod(mj));
+    else { Mod dm{}; dm.p = mj; h.dst_mod.push_back(dm); }
+    for (uint32_t i = 0; i < h.ks; ++i)
+      h.B[(size_t)i * h.kd + j] = fold_inv ? h_inv(src[i] % mj, mj) : h_prod_mod(src, (int)i, mj);
+    h.Mmod[j] = fold_inv ? 1u : h_prod_mod(src, -1, mj);
+  }
+  return h;
+}
+
+int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
+  int e;
+  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint64_t* fx; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* Mm;
+  if ((e = upload(c, h.src_mod, &sm))) return e;
+  if ((e = upload(c, h.dst_mod, &dm))) return e;
+  if ((e = upload(c, h.zmul, &zm))) return e;
+  if ((e = upload(c, h.xmul, &xm))) return e;
+  if ((e = upload(c, h.fix, &fx))) return e;
+  if ((e = upload(c, h.ginv, &gi))) return e;
+  if ((e = upload(c, h.half, &hf))) return e;
+  if ((e = upload(c, h.B, &B))) return e;
+  if ((e = upload(c, h.Mmod, &Mm))) return e;
+  d->ks = h.ks; d->kd = h.kd;
+  d->src_mod = sm; d->dst_mod = dm; d->zmul = zm; d->xmul = xm; d->fix = fx;
+  d->ginv = gi; d->half = hf; d->B = B; d->Mmod = Mm;
+  return 0;
+}
+
+int build_tables(hcnn_ctx* c) {
+  const uint32_t n = c->n, L = c->k + c->kp;
+  std::vector<uint32_t> all = c->q;
+  all.insert(all.end(), c->p.begin(), c->p.end());
+
+  std::vector<Mod> mods;
+  std::vector<NttLimb> limbs;
+  std::vector<ShoupConst> twf((size_t)L * n), twi((size_t)L * n);
+  std::vector<uint32_t> pw(2 * (size_t)n);
+  for (uint32_t l = 0; l < L; ++l) {
+    const uint32_t p = all[l];
+    const uint32_t psi = h_root_of_unity(n, p);
+    uint64_t v = 1;
+    for (uint32_t e = 0; e < 2 * n; ++e) { pw[e] = (uint32_t)v; v = v * psi % p; }
+    twf[(size_t)l * n] = h_shoup(0, p);
+    twi[(size_t)l * n] = h_shoup(0, p);
+    for (uint32_t node = 1; node < n; ++node) {
+      const uint32_t e = h_brev(node, (int)c->logn);
+      twf[(size_t)l * n + node] = h_shoup(pw[e], p);
+      twi[(size_t)l * n + node] = h_shoup(pw[2 * n - e], p);
+    }
+    NttLimb nl;
+    nl.m = h_mod(p);
+    const uint32_t ninv = h_inv(n % p, p);
+    nl.ninv = h_shoup(ninv, p);
+    nl.w1ninv = h_shoup(h_mulmod(twi[(size_t)l * n + 1].w, ninv, p), p);
+    mods.push_back(nl.m);
+    limbs.push_back(nl);
+  }
+  int e;
+  if ((e = upload(c, mods, &c->d_mods))) return e;
+  if ((e = upload(c, limbs, &c->d_limbs))) return e;
+  if ((e = upload(c, twf, &c->d_tw_fwd))) return e;
+  if ((e = upload(c, twi, &c->d_tw_inv))) return e;
+
+  // floor(q/t) mod q_l = -(q mod t) * t^-1 mod q_l   (q = 0 mod q_l)
+  const uint32_t q_mod_t = h_prod_mod(c->q, -1, c->t);
+  std::vector<ShoupConst> delta;
+  for (uint32_t l = 0; l < c->k; ++l) {
+    const uint32_t ql = c->q[l];
+    const uint32_t v = h_mulmod((ql - q_mod_t % ql) % ql, h_inv(c->t % ql, ql), ql);
+    delta.push_back(h_shoup(v, ql));
+  }
+  if ((e = upload(c, delta, &c->d_delta))) return e;
+
+  // decryption: r = [t*x]_q converted to the modulus t
+  {
+    BConvHost h = make_bconv(c->q, std::vector<uint32_t>{c->t}, c->t, false, false);
+    if ((e = upload_bconv(c, h, &c->dec))) return e;
+    const uint32_t qinv_t = h_inv(q_mod_t, c->t);
+    c->neg_qinv_t = (c->t - qinv_t) % c->t;
+  }
+  if (c->kp) {
+    BConvHost h_ext = make_bconv(c->q, c->p, 1, false, true);
+    BConvHost h_to_p = make_bconv(c->q, c->p, c->t, true, true);
+    BConvHost h_to_q = make_bconv(c->p, c->q, 1, false, true);
+    if ((e = upload_bconv(c, h_ext, &c->ext))) return e;
+    if ((e = upload_bconv(c, h_to_p, &c->to_p))) return e;
+    if ((e = upload_bconv(c, h_to_q, &c->to_q))) return e;
+    std::vector<ShoupConst> tq;
+    for (uint32_t j = 0; j < c->kp; ++j) {
+      const uint32_t pj = c->p[j];
+      tq.push_back(h_shoup(h_mulmod(c->t % pj, h_inv(h_prod_mod(c->q, -1, pj), pj), pj), pj));
+    }
+    if ((e = upload(c, tq, &c->d_tq_inv))) return e;
+  }
+  std::vector<unsigned long long> zeros(2, 0);
+  if ((e = upload(c, zeros, &c->d_counters))) return e;
+  return 0;
+}
+
+int ensure_scratch(hcnn_ctx* c, size_t bytes) {
+  if (bytes <= c->scratch_bytes) return 0;
+  if (c->scratch) {
+    int e = stream_sync(c->stream);
+    if (e) return e;
+    dev_free(c->scratch);
+    c->scratch = nullptr;
+    c->scratch_bytes = 0;
+  }
+  void* ptr = nullptr;
+  int e = dev_malloc(&ptr, bytes);
+  if (e) return e;
+  c->scratch = (uint32_t*)ptr;
+  c->scratch_bytes = bytes;
+  return 0;
+}
+
+// ---------------------------------------------------------------- NTT dispatch
+struct NttRows {
+  const uint32_t* in;
+  uint32_t* out;
+  size_t rows;
+  uint32_t cycle, limb_base;
+  uint32_t in_group_rows, in_row0, out_group_rows, out_row0;
+};
+
+template <int LOGN, int LOGR>
+int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse) {
+  NttArgs a;
+  a.in = r.in; a.out = r.out;
+  a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
+  a.limbs = c->d_limbs;
+  a.limb_cycle = r.cycle; a.limb_base = r.limb_base;
+  a.in_group_rows = r.in_group_rows; a.in_row0 = r.in_row0;
+  a.out_group_rows = r.out_group_rows; a.out_row0 = r.out_row0;
+  const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;
+  if (inverse) return launch<NttInv<LOGN, LOGR>>(c->stream, r.rows, lds, a);
+  return launch<NttFwd<LOGN, LOGR>>(c->stream, r.rows, lds, a);
+}
+
+int ntt_rows(hcnn_ctx* c, const NttRows& r, bool inverse) {
+  switch (c->logn) {
+    case 10: return ntt_launch<10, 4>(c, r, inverse);
+    case 11: return ntt_launch<11, 4>(c, r, inverse);
+    case 12: return ntt_launch<12, 4>(c, r, inverse);
+    case 13: return ntt_launch<13, 5>(c, r, inverse);
+    case 14: return ntt_launch<14, 5>(c, r, inverse);
+    case 15: return ntt_launch<15, 5>(c, r, inverse);
+  }
+  return HCNN_ERR_N;
+}
+
+// dense rows [rows][n], limb = base + r % cycle
+int ntt_dense(hcnn_ctx* c, const uint32_t* in, uint32_t* out, size_t rows, uint32_t cycle, bool inverse,
+              uint32_t limb_base = 0) {
+  NttRows r{in, out, rows, cycle, limb_base, cycle, 0, cycle, 0};
+  return ntt_rows(c, r, inverse);
+}
+
+template <int FT>
+int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
+  return launch<MacKernel<FT>>(c->stream, grid, 0, a);
+}
+
+int mac_dispatch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
+  switch (a.F) {
+    case 1: return mac_launch<1>(c, grid, a);
+    case 2: return mac_launch<2>(c, grid, a);
+    case 3: return mac_launch<3>(c, grid, a);
+    case 4: return mac_launch<4>(c, grid, a);
+    case 5: return mac_launch<5>(c, grid, a);
+    case 6: return mac_launch<6>(c, grid, a);
+    case 7: return mac_launch<7>(c, grid, a);
+    case 8: return mac_launch<8>(c, grid, a);
+    case 9: return mac_launch<9>(c, grid, a);
+    case 10: return mac_launch<10>(c, grid, a);
+    case 11: return mac_launch<11>(c, grid, a);
+    case 12: return mac_launch<12>(c, grid, a);
+    case 13: return mac_launch<13>(c, grid, a);
+    case 14: return mac_launch<14>(c, grid, a);
+    case 15: return mac_launch<15>(c, grid, a);
+    case 16: return mac_launch<16>(c, grid, a);
+  }
+  return HCNN_ERR_ARG;
+}
+
+}  // namespace
+
+// ================================================================= C ABI
+extern "C" {
+
+int hcnn_gen_primes(uint32_t n, uint32_t count, uint32_t* primes_host) {
+  if (!primes_host) return HCNN_ERR_NULL;
+  if (!valid_n(n)) return HCNN_ERR_N;
+  if (count == 0 || count > 2 * HCNN_MAX_LIMBS) return HCNN_ERR_ARG;
+  const uint32_t step = 2 * n;
+  uint32_t c = ((1u << 30) - 2) / step * step + 1;
+  uint32_t found = 0;
+  while (found < count) {
+    if (c <= (1u << 29)) return HCNN_ERR_ARG;
+    if (h_is_prime(c)) primes_host[found++] = c;
+    c -= step;
+  }
+  return HCNN_OK;
+}
+
+int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q, uint32_t t, const uint32_t* cand,
+                       uint32_t n_cand, uint32_t* k_aux_out) {
+  if (!q || !cand || !k_aux_out) return HCNN_ERR_NULL;
+  if (!valid_n(n)) return HCNN_ERR_N;
+  if (k == 0 || k > HCNN_MAX_LIMBS || n_cand == 0 || n_cand > 2 * HCNN_MAX_LIMBS) return HCNN_ERR_ARG;
+  int e = check_primes(n, q, k, cand, n_cand);
+  if (e) return e;
+  for (uint32_t kp = 1; kp <= n_cand && kp <= HCNN_MAX_LIMBS; ++kp) {
+    if (aux_sufficient(n, q, k, t, cand, kp)) {
+      *k_aux_out = kp;
+      return HCNN_OK;
+    }
+  }
+  return HCNN_ERR_AUX;
+}
+
+int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, uint32_t k_aux,
+                    const uint32_t* p, uint32_t t, void* hip_stream) {
+  if (!out || !q || (k_aux && !p)) return HCNN_ERR_NULL;
+  *out = nullptr;
+  if (!valid_n(n)) return HCNN_ERR_N;
+  if (k == 0 || k > HCNN_MAX_LIMBS || k_aux > HCNN_MAX_LIMBS) return HCNN_ERR_ARG;
+  int e = check_primes(n, q, k, p, k_aux);
+  if (e) return e;
+  if (t < 2 || t >= (1u << 29) || !h_is_prime(t)) return HCNN_ERR_T;
+  if (k_aux && !aux_sufficient(n, q, k, t, p, k_aux)) return HCNN_ERR_AUX;
+
+  hcnn_ctx* c = new (std::nothrow) hcnn_ctx();
+  if (!c) return HCNN_ERR_ARG;
+  c->n = n;
+  while ((1u << c->logn) < n) ++c->logn;
+  c->k = k; c->kp = k_aux; c->t = t;
+  c->q.assign(q, q + k);
+  if (k_aux) c->p.assign(p, p + k_aux);
+  c->stream = (hcnn_stream_t)hip_stream;
+  c->max_lds = max_lds_bytes();
+  if (c->max_lds < (size_t)n * 4) {
+    delete c;
+    return HCNN_ERR_NODEVICE;
+  }
+  e = build_tables(c);
+  if (e) {
+    hcnn_ctx_destroy(c);
+    return e;
+  }
+  *out = c;
+  return HCNN_OK;
+}
+
+int hcnn_ctx_destroy(hcnn_ctx* c) {
+  if (!c) return HCNN_ERR_NULL;
+  stream_sync(c->stream);
+  for (void* p : c->owned) dev_free(p);
+  if (c->d_evk_hat) dev_free(c->d_evk_hat);
+  if (c->scratch) dev_free(c->scratch);
+  delete c;
+  return HCNN_OK;
+}
+
+int hcnn_set_stream(hcnn_ctx* c, void* hip_stream) {
+  if (!c) return HCNN_ERR_NULL;
+  int e = stream_sync(c->stream);
+  if (e) return e;
+  c->stream = (hcnn_stream_t)hip_stream;
+  return HCNN_OK;
+}
+
+int hcnn_set_relin_key(hcnn_ctx* c, const uint32_t* evk_dev) {
+  if (!c || !evk_dev) return HCNN_ERR_NULL;
+  if (!aligned16(evk_dev)) return HCNN_ERR_ALIGN;
+  const size_t rows = (size_t)c->k * 2 * c->k;
+  if (!c->d_evk_hat) {
+    void* ptr = nullptr;
+    int e = dev_malloc(&ptr, rows * c->n * 4);
+    if (e) return e;
+    c->d_evk_hat = (uint32_t*)ptr;
+  }
+  int e = ntt_dense(c, evk_dev, c->d_evk_hat, rows, c->k, false);
+  if (e) return e;
+  c->has_key = true;
+  return HCNN_OK;
+}
+
+int hcnn_ntt_fwd(hcnn_ctx* c, uint32_t* polys_dev, size_t n_polys) {
+  if (!c || !polys_dev) return HCNN_ERR_NULL;
+  if (!aligned16(polys_dev)) return HCNN_ERR_ALIGN;
+  if (n_polys > (size_t)0x7fffffff / c->k) return HCNN_ERR_ARG;
+  return ntt_dense(c, polys_dev, polys_dev, n_polys * c->k, c->k, false);
+}
+
+int hcnn_ntt_inv(hcnn_ctx* c, uint32_t* polys_dev, size_t n_polys) {
+  if (!c || !polys_dev) return HCNN_ERR_NULL;
+  if (!aligned16(polys_dev)) return HCNN_ERR_ALIGN;
+  if (n_polys > (size_t)0x7fffffff / c->k) return HCNN_ERR_ARG;
+  return ntt_dense(c, polys_dev, polys_dev, n_polys * c->k, c->k, true);
+}
+
+int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint32_t* idx, const int32_t* w,
+                       int32_t w_abs_max, size_t G, size_t F, size_t T, uint32_t* out) {
+  if (!c || !in || !idx || !w || !out) return HCNN_ERR_NULL;
+  if (!aligned16(in) || !aligned16(out)) return HCNN_ERR_ALIGN;
+  if (n_in == 0 || n_in > 0xffffffffull || F == 0 || F > HCNN_MAX_FILTERS || T == 0 || T > 0xffffffffull ||
+      w_abs_max < 0)
+    return HCNN_ERR_ARG;
+  if (G == 0) return HCNN_OK;
+  const size_t ct_words = (size_t)2 * c->k * c->n;
+  const size_t tiles = ct_words / (kEwThreads * kEwVec);
+  if (G > (size_t)0x7fffffff / tiles) return HCNN_ERR_ARG;
+  MacArgs a;
+  a.in = in; a.idx = idx; a.w = w; a.out = out;
+  a.mods = c->d_mods; a.k = c->k; a.n = c->n;
+  a.n_in = (uint32_t)n_in; a.G = (uint32_t)G; a.F = (uint32_t)F; a.T = (uint32_t)T;
+  a.w_abs_max = w_abs_max;
+  // partial sums stay below 2^63: chunk * w_abs_max * 2^30 + 2^30 <= 2^63
+  const uint64_t wm = w_abs_max > 0 ? (uint64_t)w_abs_max : 1;
+  uint64_t chunk = ((1ull << 33) - 1) / wm;
+  if (chunk > T) chunk = T;
+  a.chunk = (uint32_t)chunk;
+  a.bad_counter = c->d_counters + 1;
+  return mac_dispatch(c, G * tiles, a);
+}
+
+int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t* out) {
+  if (!c || !in || !out) return HCNN_ERR_NULL;
+  if (!aligned16(in) || !aligned16(out)) return HCNN_ERR_ALIGN;
+  if (c->kp == 0) return HCNN_ERR_AUX;
+  if (!c->has_key) return HCNN_ERR_NOKEY;
+  if (n_ct == 0) return HCNN_OK;
+  const uint32_t k = c->k, kp = c->kp, L = k + kp, n = c->n;
+  const size_t rn = n;
+  const size_t words_per_ct = ((size_t)2 * L + 3 * L + 3 * k + (size_t)k * k + 2 * k) * rn;
+  size_t C = c->square_chunk;
+  if (C == 0) {
+    const size_t budget = (size_t)3 << 29;   // 1.5 GiB of scratch
+    C = budget / (words_per_ct * 4);
+    if (C > 256) C = 256;
+  }
+  if (C < 1) C = 1;
+  if (C > n_ct) C = n_ct;
+  const size_t need_lds_scale = ScaleKernel::lds_bytes(k, kp);
+  if (need_lds_scale > c->max_lds) return HCNN_ERR_NODEVICE;
+  int e = ensure_scratch(c, C * words_per_ct * 4);
+  if (e) return e;
+  uint32_t* ext = c->scratch;
+  uint32_t* d = ext + C * 2 * L * rn;
+  uint32_t* y = d + C * 3 * L * rn;
+  uint32_t* dig = y + C * 3 * k * rn;
+  uint32_t* acc = dig + C * k * k * rn;
+  const size_t ct_words = (size_t)2 * k * rn;
+  const size_t bpp = n / kEwThreads;                 // blocks per polynomial, 1 coefficient / thread
+  const size_t bpr = n / (kEwThreads * kEwVec);      // blocks per row, 4 coefficients / thread
+
+  for (size_t c0 = 0; c0 < n_ct; c0 += C) {
+    const size_t cc = std::min(C, n_ct - c0);
+    // 1. centred lift of c0, c1 extended to the auxiliary primes
+    ExtArgs ea;
+    ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
+    ea.fallback_counter = c->d_counters;
+    if ((e = launch<ExtKernel>(c->stream, cc * 2 * bpp, ExtKernel::lds_bytes(k), ea))) return e;
+    // 2. forward NTT over all k + k' limbs
+    if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false))) return e;
+    // 3. tensor: (c0^2, 2 c0 c1, c1^2)
+    TensorArgs ta;
+    ta.ext = ext; ta.d = d; ta.mods = c->d_mods; ta.L = L; ta.n = n;
+    if ((e = launch<TensorSqKernel>(c->stream, cc * L * bpr, 0, ta))) return e;
+    // 4. back to coefficients: the integer tensor, known mod q*p
+    if ((e = ntt_dense(c, d, d, cc * 3 * L, L, true))) return e;
+    // 5. y = round(t/q * d) mod q
+    ScaleArgs sa;
+    sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
+    sa.band = c->band; sa.fallback_counter = c->d_counters;
+    if ((e = launch<ScaleKernel>(c->stream, cc * 3 * bpp, need_lds_scale, sa))) return e;
+    // 6. RNS digits of y2, each reduced modulo every q_j, then transformed
+    DigitArgs da;
+    da.y = y; da.dig = dig; da.mods = c->d_mods; da.k = k; da.n = n;
+    if ((e = launch<DigitKernel>(c->stream, cc * k * bpr, 0, da))) return e;
+    if ((e = ntt_dense(c, dig, dig, cc * k * k, k, false))) return e;
+    // 7. inner product with the evaluation key
+    RelinMacArgs ra;
+    ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
+    if ((e = launch<RelinMacKernel>(c->stream, cc * k * bpr, 0, ra))) return e;
+    if ((e = ntt_dense(c, acc, acc, cc * 2 * k, k, true))) return e;
+    // 8. c'_b = y_b + sum_i evk[i][b] * digit_i
+    RelinAddArgs aa;
+    aa.y = y; aa.acc = acc; aa.out = out + c0 * ct_words; aa.mods = c->d_mods; aa.k = k; aa.n = n;
+    if ((e = launch<RelinAddKernel>(c->stream, cc * 2 * k * bpr, 0, aa))) return e;
+  }
+  return HCNN_OK;
+}
+
+// ---------------------------------------------------------------- test helpers
+int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t* e_small, const uint32_t* a_evk,
+                const int32_t* e_evk, uint32_t* pk_out, uint32_t* evk_out) {
+  if (!c || !s || !a || !e_small || !pk_out) return HCNN_ERR_NULL;
+  if (evk_out && (!a_evk || !e_evk)) return HCNN_ERR_NULL;
+  if (!aligned16(a) || !aligned16(pk_out) || !aligned16(a_evk) || !aligned16(evk_out)) return HCNN_ERR_ALIGN;
+  const uint32_t k = c->k, n = c->n;
+  const size_t rn = n, poly = (size_t)k * rn;
+  const size_t bpp = n / kEwThreads;
+  // scratch: s_hat [k][n] | s2 [k][n] | tmp [k*k][n]
+  int e = ensure_scratch(c, (2 * poly + (size_t)k * poly) * 4);
+  if (e) return e;
+  uint32_t* s_hat = c->scratch;
+  uint32_t* s2 = s_hat + poly;
+  uint32_t* tmp = s2 + poly;
+
+  SmallToRnsArgs sr{s, s_hat, c->d_mods, k, n};
+  if ((e = launch<SmallToRnsKernel>(c->stream, bpp, 0, sr))) return e;
+  if ((e = ntt_dense(c, s_hat, s_hat, k, k, false))) return e;
+
+  // pk = (e - a*s, a)
+  if ((e = ntt_dense(c, a, tmp, k, k, false))) return e;
+  PointMulArgs pm{tmp, s_hat, tmp, c->d_mods, k, n, k, k, 1u};
+  if ((e = launch<PointMulKernel>(c->stream, (size_t)k * bpp, 0, pm))) return e;
+  if ((e = ntt_dense(c, tmp, tmp, k, k, true))) return e;
+  AddSmallArgs as{tmp, e_small, nullptr, nullptr, pk_out, c->d_mods, k, n, 0u, 2 * k, 0u};
+  if ((e = launch<AddSmallKernel>(c->stream, (size_t)k * bpp, 0, as))) return e;
+  if ((e = copy_d2d(pk_out + poly, a, poly * 4, c->stream))) return e;
+  if (!evk_out) return HCNN_OK;
+
+  // s^2, coefficient domain
+  PointMulArgs p2{s_hat, s_hat, s2, c->d_mods, k, n, k, k, 0u};
+  if ((e = launch<PointMulKernel>(c->stream, (size_t)k * bpp, 0, p2))) return e;
+  if ((e = ntt_dense(c, s2, s2, k, k, true))) return e;
+  // evk[i][0] = g_i*s^2 - (a_i*s + e_i), evk[i][1] = a_i, all components at once
+  if ((e = ntt_dense(c, a_evk, tmp, (size_t)k * k, k, false))) return e;
+  PointMulArgs pe{tmp, s_hat, tmp, c->d_mods, k, n, k * k, k, 1u};
+  if ((e = launch<PointMulKernel>(c->stream, (size_t)k * k * bpp, 0, pe))) return e;
+  if ((e = ntt_dense(c, tmp, tmp, (size_t)k * k, k, true))) return e;
+  AddSmallArgs ae{tmp, e_evk, nullptr, nullptr, evk_out, c->d_mods, k, n, 1u, 2 * k, 0u};
+  if ((e = launch<AddSmallKernel>(c->stream, (size_t)k * k * bpp, 0, ae))) return e;
+  AddDiagArgs ad{evk_out, s2, c->d_mods, k, n};
+  if ((e = launch<AddDiagKernel>(c->stream, (size_t)k * bpp, 0, ad))) return e;
+  for (uint32_t i = 0; i < k; ++i)
+    if ((e = copy_d2d(evk_out + ((size_t)i * 2 + 1) * poly, a_evk + (size_t)i * poly, poly * 4, c->stream))) return e;
+  return HCNN_OK;
+}
+
+int hcnn_encrypt(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const int32_t* u, const int32_t* e1,
+                 const int32_t* e2, size_t n_ct, uint32_t* ct_out) {
+  if (!c || !pk || !m || !u || !e1 || !e2 || !ct_out) return HCNN_ERR_NULL;
+  if (!aligned16(pk) || !aligned16(ct_out)) return HCNN_ERR_ALIGN;
+  if (n_ct == 0) return HCNN_OK;
+  const uint32_t k = c->k, n = c->n;
+  const size_t rn = n, poly = (size_t)k * rn;
+  const size_t bpp = n / kEwThreads;
+  const size_t C = std::min<size_t>(n_ct, 64);
+  // scratch: pk_hat [2][k][n] | u_hat [C][k][n] | prod [C][k][n]
+  int e = ensure_scratch(c, (2 * poly + 2 * C * poly) * 4);
+  if (e) return e;
+  uint32_t* pk_hat = c->scratch;
+  uint32_t* u_hat = pk_hat + 2 * poly;
+  uint32_t* prod = u_hat + C * poly;
+  if ((e = ntt_dense(c, pk, pk_hat, 2 * (size_t)k, k, false))) return e;
+  for (size_t c0 = 0; c0 < n_ct; c0 += C) {
+    const size_t cc = std::min(C, n_ct - c0);
+    SmallToRnsArgs sr{u + c0 * rn, u_hat, c->d_mods, k, n};
+    if ((e = launch<SmallToRnsKernel>(c->stream, cc * bpp, 0, sr))) return e;
+    if ((e = ntt_dense(c, u_hat, u_hat, cc * k, k, false))) return e;
+    for (uint32_t b = 0; b < 2; ++b) {
+      PointMulArgs pm{u_hat, pk_hat + b * poly, prod, c->d_mods, k, n, (uint32_t)(cc * k), k, 0u};
+      if ((e = launch<PointMulKernel>(c->stream, cc * k * bpp, 0, pm))) return e;
+      if ((e = ntt_dense(c, prod, prod, cc * k, k, true))) return e;
+      AddSmallArgs as{prod, (b == 0 ? e1 : e2) + c0 * rn, b == 0 ? m + c0 * rn : nullptr,
+                      b == 0 ? c->d_delta : nullptr, ct_out + c0 * 2 * poly, c->d_mods, k, n, 0u, 2 * k, b * k};
+      if ((e = launch<AddSmallKernel>(c->stream, cc * k * bpp, 0, as))) return e;
+    }
+  }
+  return HCNN_OK;
+}
+
+int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint32_t* m_out) {
+  if (!c || !sk || !ct || !m_out) return HCNN_ERR_NULL;
+  if (!aligned16(ct)) return HCNN_ERR_ALIGN;
+  if (n_ct == 0) return HCNN_OK;
+  const uint32_t k = c->k, n = c->n;
+  const size_t rn = n, poly = (size_t)k * rn;
+  const size_t bpp = n / kEwThreads;
+  const size_t C = std::min<size_t>(n_ct, 64);
+  // scratch: s_hat [k][n] | x [C][k][n]
+  int e = ensure_scratch(c, (poly + C * poly) * 4);
+  if (e) return e;
+  uint32_t* s_hat = c->scratch;
+  uint32_t* x = s_hat + poly;
+  SmallToRnsArgs sr{sk, s_hat, c->d_mods, k, n};
+  if ((e = launch<SmallToRnsKernel>(c->stream, bpp, 0, sr))) return e;
+  if ((e = ntt_dense(c, s_hat, s_hat, k, k, false))) return e;
+  for (size_t c0 = 0; c0 < n_ct; c0 += C) {
+    const size_t cc = std::min(C, n_ct - c0);
+    const uint32_t* cts = ct + c0 * 2 * poly;
+    // x = NTT(c1) picked out of every ciphertext
+    NttRows r{cts, x, cc * k, k, 0, 2 * k, k, k, 0};
+    if ((e = ntt_rows(c, r, false))) return e;
+    PointMulArgs pm{x, s_hat, x, c->d_mods, k, n, (uint32_t)(cc * k), k, 0u};
+    if ((e = launch<PointMulKernel>(c->stream, cc * k * bpp, 0, pm))) return e;
+    if ((e = ntt_dense(c, x, x, cc * k, k, true))) return e;
+    AddRowsArgs ar{cts, x, x, c->d_mods, k, n, 2 * k, 0u};
+    if ((e = launch<AddRowsKernel>(c->stream, cc * k * bpp, 0, ar))) return e;
+    DecRoundArgs da;
+    da.x = x; da.m_out = m_out + c0 * rn; da.bc = c->dec; da.t = c->t; da.neg_qinv_t = c->neg_qinv_t; da.n = n;
+    da.band = c->band; da.fallback_counter = c->d_counters;
+    if ((e = launch<DecRoundKernel>(c->stream, cc * bpp, DecRoundKernel::lds_bytes(k), da))) return e;
+  }
+  return HCNN_OK;
+}
+
+// ---------------------------------------------------------------- diagnostics
+int hcnn_get_stat(hcnn_ctx* c, int which, uint64_t* out) {
+  if (!c || !out) return HCNN_ERR_NULL;
+  if (which == HCNN_STAT_SCRATCH_BYTES) {
+    *out = c->scratch_bytes;
+    return HCNN_OK;
+  }
+  if (which != HCNN_STAT_EXACT_FALLBACKS && which != HCNN_STAT_BAD_INPUT) return HCNN_ERR_ARG;
+  unsigned long long v[2] = {0, 0};
+  int e = copy_d2h(v, c->d_counters, sizeof(v), c->stream);
+  if (e) return e;
+  *out = v[which];
+  return HCNN_OK;
+}
+
+int hcnn_reset_stats(hcnn_ctx* c) {
+  if (!c) return HCNN_ERR_NULL;
+  return dev_memset(c->d_counters, 0, 2 * sizeof(unsigned long long), c->stream);
+}
+
+int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
+  if (!c) return HCNN_ERR_NULL;
+  switch (which) {
+    case HCNN_OPT_AMBIGUITY_BAND:
+      if (value < 4ull * HCNN_MAX_LIMBS) return HCNN_ERR_ARG;   // never below the error bound of the estimate
+      c->band = value;
+      return HCNN_OK;
+    case HCNN_OPT_SQUARE_CHUNK:
+      c->square_chunk = value;
+      return HCNN_OK;
+  }
+  return HCNN_ERR_ARG;
+}
+
+const char* hcnn_strerror(int code) {
+  switch (code) {
+    case HCNN_OK: return "ok";
+    case HCNN_ERR_NULL: return "null pointer";
+    case HCNN_ERR_N: return "n must be a power of two in [1024, 32768]";
+    case HCNN_ERR_PRIME: return "modulus is not a distinct prime in (2^29, 2^30) congruent to 1 mod 2n";
+    case HCNN_ERR_T: return "t must be a prime below 2^29";
+    case HCNN_ERR_AUX: return "auxiliary basis missing or too small (need prod p > t*n*q + 1)";
+    case HCNN_ERR_ARG: return "invalid count, size or option";
+    case HCNN_ERR_NOKEY: return "relinearisation key not set";
+    case HCNN_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case HCNN_ERR_NODEVICE: return "no usable device or LDS too small";
+  }
+#ifndef HCNN_HOSTEMU
+  if (code > 0) return hipGetErrorString((hipError_t)code);
+#endif
+  return "unknown error";
+}
+
+}  // extern "C"

@@ -1,0 +1,209 @@
+// Batched negacyclic NTT over 30-bit primes, one workgroup per (polynomial, limb) row.
+//
+// Forward: Cooley-Tukey butterflies with the powers of psi merged into the
+// twiddles, natural order in, bit-reversed order out (index j holds the value at
+// psi^(2*brev(j)+1)).  Inverse: Gentleman-Sande butterflies with the inverse
+// twiddles in the reverse stage order, n^-1 merged into the last stage.
+//
+// The log2(n) stages are cut into passes of at most LOGR stages.  In a pass every
+// thread keeps R = 2^LOGR residues in registers and runs complete radix-2^NS
+// butterfly networks on them; between passes the row lives in LDS (one barrier per
+// pass).  The first pass reads HBM with unit stride across lanes, the last pass
+// writes HBM.  Residues stay lazily reduced (forward: [0,4p), inverse: [0,2p)) and
+// are made canonical only on the way out.
+//
+// Twiddle table layout: tw[limb][node], node in [1, n): the butterflies of the stage
+// with m groups use nodes m .. 2m-1 (node m+i = psi^brev_{log n}(m+i)); a radix-2^NS
+// network rooted at node r uses the sub-tree r, 2r, 2r+1, 4r, ...
+#pragma once
+#include "modarith.h"
+
+namespace hcnn {
+
+struct NttLimb {
+  Mod m;
+  ShoupConst ninv;    // n^-1 mod p
+  ShoupConst w1ninv;  // (inverse twiddle of node 1) * n^-1 mod p
+};
+
+// Row r (= workgroup index) belongs to group r / limb_cycle and limb limb_base + r % limb_cycle.
+// Its data sits at row (group * group_rows + row0 + r % limb_cycle) of the in / out arrays, so a
+// launch can pick one polynomial out of every ciphertext of a batch.
+struct NttArgs {
+  const uint32_t* in;
+  uint32_t* out;            // may equal `in`
+  const ShoupConst* tw;     // [L][n] node table (forward or inverse)
+  const NttLimb* limbs;     // [L]
+  uint32_t limb_cycle;
+  uint32_t limb_base;
+  uint32_t in_group_rows, in_row0;
+  uint32_t out_group_rows, out_row0;
+};
+
+HCNN_HD size_t ntt_row(uint32_t r, uint32_t cycle, uint32_t group_rows, uint32_t row0) {
+  return (size_t)(r / cycle) * group_rows + row0 + r % cycle;
+}
+
+// LDS index swizzle: spreads power-of-two strides over the 32 banks.
+HCNN_HD uint32_t lds_swz(uint32_t i) { return i ^ ((i >> 5) & 31u); }
+
+template <int LOGN, int LOGR>
+struct NttGeom {
+  static constexpr int N = 1 << LOGN;
+  static constexpr int R = 1 << LOGR;
+  static constexpr int kThreads = N / R;
+  static constexpr int kPhases = (LOGN + LOGR - 1) / LOGR;
+  static constexpr size_t kLdsBytes = (size_t)N * 4;
+  // forward pass PH covers stages [s0(PH), s0(PH)+ns(PH))
+  static constexpr int s0(int ph) { return ph * LOGR; }
+  static constexpr int ns(int ph) { return ph < kPhases - 1 ? LOGR : LOGN - LOGR * (kPhases - 1); }
+};
+
+// ------------------------------------------------------------------------- forward
+template <int LOGN, int LOGR>
+struct NttFwd {
+  using G = NttGeom<LOGN, LOGR>;
+  static constexpr int kThreads = G::kThreads;
+  static constexpr int kPhases = G::kPhases;
+  struct Regs {};
+
+  template <int PH>
+  HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+    constexpr int N = G::N, R = G::R;
+    constexpr int S0 = G::s0(PH), NS = G::ns(PH), NET = 1 << NS, C = R / NET;
+    constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
+    constexpr bool kFirst = PH == 0, kLast = PH == kPhases - 1;
+
+    const uint32_t limb = a.limb_base + bid % a.limb_cycle;
+    const NttLimb& L = a.limbs[limb];
+    const uint32_t p = L.m.p, two_p = 2 * L.m.p;
+    const ShoupConst* tw = a.tw + (size_t)limb * N;
+    const uint32_t* gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+    uint32_t* gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      const uint32_t nu = (uint32_t)tid + (uint32_t)kThreads * c;   // network id
+      const uint32_t o = nu & (TLAST - 1), i = nu >> LOG_TLAST;
+      const uint32_t base = i * (uint32_t)(NET * TLAST) + o;        // element e at base + e*TLAST
+      uint32_t v[NET];
+#pragma unroll
+      for (int e = 0; e < NET; ++e) {
+        const uint32_t idx = base + (uint32_t)e * TLAST;
+        v[e] = kFirst ? gin[idx] : lds[lds_swz(idx)];
+      }
+      const uint32_t root = (1u << S0) + i;
+#pragma unroll
+      for (int l = 0; l < NS; ++l) {
+        const int half = NET >> (l + 1);
+#pragma unroll
+        for (int h = 0; h < (1 << l); ++h) {
+          const ShoupConst w = tw[(root << l) + h];
+#pragma unroll
+          for (int x = 0; x < half; ++x) {
+            const int ia = h * 2 * half + x, ib = ia + half;
+            const uint32_t X = csub(v[ia], two_p);                      // [0, 2p)
+            const uint32_t T = shoup_lazy(v[ib], w.w, w.ws, p);        // [0, 2p)
+            v[ia] = X + T;                                             // [0, 4p)
+            v[ib] = X + two_p - T;                                     // (0, 4p)
+          }
+        }
+      }
+      if constexpr (kLast && NET >= 4) {
+        // TLAST == 1: the network is NET consecutive coefficients -> 16-byte stores
+        U4* g4 = reinterpret_cast<U4*>(gout + base);
+#pragma unroll
+        for (int e = 0; e < NET; e += 4) {
+          U4 t;
+          t.x = csub(csub(v[e + 0], two_p), p);
+          t.y = csub(csub(v[e + 1], two_p), p);
+          t.z = csub(csub(v[e + 2], two_p), p);
+          t.w = csub(csub(v[e + 3], two_p), p);
+          g4[e / 4] = t;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < NET; ++e) {
+          const uint32_t idx = base + (uint32_t)e * TLAST;
+          if (kLast) gout[idx] = csub(csub(v[e], two_p), p);
+          else       lds[lds_swz(idx)] = v[e];
+        }
+      }
+    }
+  }
+};
+
+// ------------------------------------------------------------------------- inverse
+template <int LOGN, int LOGR>
+struct NttInv {
+  using G = NttGeom<LOGN, LOGR>;
+  static constexpr int kThreads = G::kThreads;
+  static constexpr int kPhases = G::kPhases;
+  struct Regs {};
+
+  template <int PHI>
+  HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+    constexpr int PH = kPhases - 1 - PHI;   // mirrors forward pass PH
+    constexpr int N = G::N, R = G::R;
+    constexpr int S0 = G::s0(PH), NS = G::ns(PH), NET = 1 << NS, C = R / NET;
+    constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
+    constexpr bool kFirst = PHI == 0, kLast = PHI == kPhases - 1;   // kLast <=> S0 == 0
+
+    const uint32_t limb = a.limb_base + bid % a.limb_cycle;
+    const NttLimb& L = a.limbs[limb];
+    const uint32_t p = L.m.p, two_p = 2 * L.m.p;
+    const ShoupConst* tw = a.tw + (size_t)limb * N;
+    const uint32_t* gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+    uint32_t* gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      const uint32_t nu = (uint32_t)tid + (uint32_t)kThreads * c;
+      const uint32_t o = nu & (TLAST - 1), i = nu >> LOG_TLAST;
+      const uint32_t base = i * (uint32_t)(NET * TLAST) + o;
+      uint32_t v[NET];
+      if constexpr (kFirst && NET >= 4) {
+        // TLAST == 1: NET consecutive coefficients -> 16-byte loads
+        const U4* g4 = reinterpret_cast<const U4*>(gin + base);
+#pragma unroll
+        for (int e = 0; e < NET; e += 4) {
+          const U4 t = g4[e / 4];
+          v[e + 0] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < NET; ++e) {
+          const uint32_t idx = base + (uint32_t)e * TLAST;
+          v[e] = kFirst ? gin[idx] : lds[lds_swz(idx)];     // [0, 2p)
+        }
+      }
+      const uint32_t root = (1u << S0) + i;
+#pragma unroll
+      for (int l = NS - 1; l >= 0; --l) {
+        const int half = NET >> (l + 1);
+        const bool top = kLast && l == 0;                 // node 1: fold in n^-1
+#pragma unroll
+        for (int h = 0; h < (1 << l); ++h) {
+          const ShoupConst w = top ? L.w1ninv : tw[(root << l) + h];
+#pragma unroll
+          for (int x = 0; x < half; ++x) {
+            const int ia = h * 2 * half + x, ib = ia + half;
+            const uint32_t X = v[ia], Y = v[ib];
+            const uint32_t S = X + Y;                                   // [0, 4p)
+            const uint32_t D = X + two_p - Y;                           // (0, 4p)
+            v[ia] = top ? shoup_lazy(S, L.ninv.w, L.ninv.ws, p) : csub(S, two_p);
+            v[ib] = shoup_lazy(D, w.w, w.ws, p);                        // [0, 2p)
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < NET; ++e) {
+        const uint32_t idx = base + (uint32_t)e * TLAST;
+        if (kLast) gout[idx] = csub(v[e], p);
+        else       lds[lds_swz(idx)] = v[e];
+      }
+    }
+  }
+};
+
+}  // namespace hcnn

@@ -1,0 +1,132 @@
+// Launch and memory shims.
+//
+// Every kernel of this library is written as a struct with
+//   kThreads                      threads per workgroup
+//   kPhases                       number of barrier-separated phases
+//   struct Regs                   per-thread state that lives across barriers
+//   template<int PH> phase(args, block, tid, lds, regs)
+// The HIP build runs the phases of one workgroup inside one __global__ function
+// with __syncthreads() between phases.  The HCNN_HOSTEMU build (used only by the
+// CPU test-suite to check kernel indexing and arithmetic before anything touches
+// a GPU) runs the same phase bodies as plain loops over blocks and threads; it is
+// a checker for the kernel sources, not a product path, and the Python binding
+// never loads it.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#ifdef HCNN_HOSTEMU
+#define HCNN_HD inline
+#define HCNN_DEVICE_CODE 0
+typedef int hcnn_hip_error_t;
+typedef void* hcnn_stream_t;
+#else
+#include <hip/hip_runtime.h>
+#define HCNN_HD __device__ __forceinline__
+typedef hipError_t hcnn_hip_error_t;
+typedef hipStream_t hcnn_stream_t;
+#endif
+
+namespace hcnn {
+
+#ifdef HCNN_HOSTEMU
+struct alignas(16) U4 { uint32_t x, y, z, w; };
+#else
+typedef uint4 U4;
+#endif
+
+#ifdef HCNN_HOSTEMU
+// ------------------------------------------------------------------ host emulation
+inline int dev_malloc(void** p, size_t bytes) {
+  *p = std::malloc(bytes ? bytes : 1);
+  return *p ? 0 : 2;
+}
+inline int dev_free(void* p) { std::free(p); return 0; }
+inline int dev_memset(void* p, int v, size_t bytes, hcnn_stream_t) { std::memset(p, v, bytes); return 0; }
+inline int copy_h2d(void* d, const void* h, size_t bytes, hcnn_stream_t) { std::memcpy(d, h, bytes); return 0; }
+inline int copy_d2h(void* h, const void* d, size_t bytes, hcnn_stream_t) { std::memcpy(h, d, bytes); return 0; }
+inline int copy_d2d(void* d, const void* s, size_t bytes, hcnn_stream_t) { std::memmove(d, s, bytes); return 0; }
+inline int stream_sync(hcnn_stream_t) { return 0; }
+inline size_t max_lds_bytes() { return 160 * 1024; }
+HCNN_HD void atomic_inc64(unsigned long long* p) { *p += 1; }
+
+template <class K, int PH>
+struct EmuPhases {
+  template <class Args>
+  static void run(const Args& a, unsigned bid, uint32_t* lds, std::vector<typename K::Regs>& regs) {
+    for (int tid = 0; tid < K::kThreads; ++tid) K::template phase<PH>(a, bid, tid, lds, regs[tid]);
+    if constexpr (PH + 1 < K::kPhases) EmuPhases<K, PH + 1>::run(a, bid, lds, regs);
+  }
+};
+
+template <class K, class Args>
+int launch(hcnn_stream_t, size_t grid, size_t lds_bytes, const Args& a) {
+  if (lds_bytes > max_lds_bytes()) return 1;
+  std::vector<uint32_t> lds(lds_bytes / 4 + 4);
+  std::vector<typename K::Regs> regs(K::kThreads);
+  for (size_t bid = 0; bid < grid; ++bid) EmuPhases<K, 0>::run(a, (unsigned)bid, lds.data(), regs);
+  return 0;
+}
+
+#else
+// ------------------------------------------------------------------ HIP
+inline int dev_malloc(void** p, size_t bytes) { return (int)hipMalloc(p, bytes ? bytes : 1); }
+inline int dev_free(void* p) { return (int)hipFree(p); }
+inline int dev_memset(void* p, int v, size_t bytes, hcnn_stream_t s) { return (int)hipMemsetAsync(p, v, bytes, s); }
+inline int copy_h2d(void* d, const void* h, size_t bytes, hcnn_stream_t s) {
+  // tables are tiny and built once: a synchronous copy keeps the host vector's lifetime simple
+  (void)s;
+  return (int)hipMemcpy(d, h, bytes, hipMemcpyHostToDevice);
+}
+inline int copy_d2h(void* h, const void* d, size_t bytes, hcnn_stream_t s) {
+  int e = (int)hipStreamSynchronize(s);
+  if (e) return e;
+  return (int)hipMemcpy(h, d, bytes, hipMemcpyDeviceToHost);
+}
+inline int copy_d2d(void* d, const void* s_, size_t bytes, hcnn_stream_t s) {
+  return (int)hipMemcpyAsync(d, s_, bytes, hipMemcpyDeviceToDevice, s);
+}
+inline int stream_sync(hcnn_stream_t s) { return (int)hipStreamSynchronize(s); }
+inline size_t max_lds_bytes() {
+  int dev = 0, v = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return 0;
+  return (size_t)v;
+}
+HCNN_HD void atomic_inc64(unsigned long long* p) { atomicAdd(p, 1ull); }
+
+template <class K, int PH, class Args>
+__device__ __forceinline__ void run_phases(const Args& a, unsigned bid, int tid, uint32_t* lds,
+                                           typename K::Regs& regs) {
+  K::template phase<PH>(a, bid, tid, lds, regs);
+  if constexpr (PH + 1 < K::kPhases) {
+    __syncthreads();
+    run_phases<K, PH + 1, Args>(a, bid, tid, lds, regs);
+  }
+}
+
+template <class K, class Args>
+__global__ void __launch_bounds__(K::kThreads) kernel_entry(const Args a) {
+  extern __shared__ __align__(16) uint32_t hcnn_lds[];
+  typename K::Regs regs;
+  run_phases<K, 0, Args>(a, blockIdx.x, (int)threadIdx.x, hcnn_lds, regs);
+}
+
+template <class K, class Args>
+int launch(hcnn_stream_t s, size_t grid, size_t lds_bytes, const Args& a) {
+  if (grid == 0) return 0;
+  if (grid > 0x7fffffffull) return (int)hipErrorInvalidConfiguration;
+  if (lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_entry<K, Args>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return (int)e;
+  }
+  hipLaunchKernelGGL((kernel_entry<K, Args>), dim3((unsigned)grid), dim3(K::kThreads), lds_bytes, s, a);
+  return (int)hipGetLastError();
+}
+#endif
+
+}  // namespace hcnn

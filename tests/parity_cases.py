@@ -1,0 +1,223 @@
+"""Parity cases shared by the CPU checker of the kernel sources (tests/emu.py) and the
+GPU tests: each function drives the C ABI through a backend and compares with the
+oracle element by element (bit-exact: everything here is integer work).
+
+A backend provides
+    lib                 the loaded C library (for the host-only helpers)
+    make_ctx(n,q,p,t)   context object with the OpsMixin methods
+    dev(np_array)       buffer usable by the context (device tensor / aligned ndarray)
+    host(buffer)        numpy uint32 view of the buffer's contents
+"""
+import numpy as np
+
+from oracle import fv
+from paper_1811_00778_amd import _capi, layers
+from workloads import generators as gen
+
+
+class Setup:
+    """Moduli from the library's own rule, checked against the oracle's rule, plus keys from the oracle."""
+
+    def __init__(self, backend, n, k, t=65537, seed_id=1, stream=0, with_keys=True):
+        self.b, self.n, self.k, self.t = backend, n, k, t
+        cand = _capi.gen_primes(backend.lib, n, k + min(32, k + 8))
+        assert cand == fv.ntt_primes(n, len(cand))
+        self.q = cand[:k]
+        k_aux = _capi.min_aux_count(backend.lib, n, self.q, t, cand[k:])
+        self.p = cand[k:k + k_aux]
+        Q, P = 1, 1
+        for v in self.q:
+            Q *= v
+        for v in self.p:
+            P *= v
+        assert P > t * n * Q + 1                       # enough range for the scaled tensor
+        assert k_aux == 1 or P // self.p[-1] <= t * n * Q + 1   # and minimal
+        self.octx = fv.Context(n, self.q, t)
+        self.ctx = backend.make_ctx(n, self.q, self.p, t)
+        self.rng = gen.rng_for(seed_id, stream)
+        if with_keys:
+            self.kr = gen.key_randomness(self.rng, self.q, n)
+            self.pk, self.evk = fv.keygen(self.octx, self.kr["s"], self.kr["a"], self.kr["e"],
+                                          self.kr["a_evk"], self.kr["e_evk"])
+
+    def encrypt_oracle(self, count, high=None):
+        high = self.t if high is None else high
+        slots = gen.slot_values(self.rng, count, self.n, high)
+        er = gen.encryption_randomness(self.rng, self.n, count)
+        polys = np.stack([fv.slot_encode(slots[i], self.n, self.t) for i in range(count)])
+        cts = np.stack([fv.encrypt(self.octx, self.pk, polys[i], er["u"][i], er["e1"][i], er["e2"][i])
+                        for i in range(count)])
+        return slots, polys, er, cts
+
+
+def check_ntt(backend, n, k, n_polys, sample_rows, seed_id=1):
+    s = Setup(backend, n, k, seed_id=seed_id, with_keys=False)
+    x = gen.uniform_residues(s.rng, s.q, n, lead=(n_polys,))
+    # corner values: 0, 1, p-1 in a few positions of the first polynomial
+    for l, p in enumerate(s.q):
+        x[0, l, 0], x[0, l, 1], x[0, l, n - 1] = 0, 1, p - 1
+    buf = backend.dev(x)
+    s.ctx.ntt_fwd(buf)
+    got = backend.host(buf).copy()
+    rows = [(i, l) for i in range(n_polys) for l in range(k)]
+    pick = rows if sample_rows is None or sample_rows >= len(rows) else \
+        [rows[j] for j in sorted(set(np.linspace(0, len(rows) - 1, sample_rows).astype(int).tolist()))]
+    for i, l in pick:
+        assert np.array_equal(got[i, l], fv.ntt_forward(x[i, l], s.q[l])), ("ntt_fwd", n, i, l)
+    for l, p in enumerate(s.q):
+        assert int(got[:, l].max()) < p                       # canonical residues
+    s.ctx.ntt_inv(buf)
+    assert np.array_equal(backend.host(buf), x), ("ntt roundtrip", n)
+    # inverse alone against the oracle's interpolation on one row
+    y = gen.uniform_residues(s.rng, s.q, n, lead=(1,))
+    buf = backend.dev(y)
+    s.ctx.ntt_inv(buf)
+    assert np.array_equal(backend.host(buf)[0, k - 1], fv.ntt_inverse(y[0, k - 1], s.q[k - 1])), ("ntt_inv", n)
+    s.ctx.close()
+
+
+def check_keygen_encrypt_decrypt(backend, n, k, count=3, seed_id=1):
+    s = Setup(backend, n, k, seed_id=seed_id)
+    kr = s.kr
+    gpk, gevk = s.ctx.keygen(backend.dev(kr["s"]), backend.dev(kr["a"]), backend.dev(kr["e"]),
+                             backend.dev(kr["a_evk"]), backend.dev(kr["e_evk"]))
+    assert np.array_equal(backend.host(gpk), s.pk), "keygen pk"
+    assert np.array_equal(backend.host(gevk), s.evk), "keygen evk"
+    slots, polys, er, cts = s.encrypt_oracle(count)
+    gcts = s.ctx.encrypt(backend.dev(s.pk), backend.dev(polys), backend.dev(er["u"]), backend.dev(er["e1"]),
+                         backend.dev(er["e2"]))
+    assert np.array_equal(backend.host(gcts), cts), "encrypt"
+    got = backend.host(s.ctx.decrypt(backend.dev(kr["s"]), gcts))
+    assert np.array_equal(got, polys), "decrypt(encrypt)"
+    want = np.stack([fv.decrypt(s.octx, kr["s"], cts[i]) for i in range(count)])
+    assert np.array_equal(got, want), "decrypt vs oracle"
+    # decrypt of noise-saturated (uniform) ciphertexts still has a defined value
+    rnd = gen.uniform_residues(s.rng, s.q, n, lead=(2, 2))
+    got = backend.host(s.ctx.decrypt(backend.dev(kr["s"]), backend.dev(rnd)))
+    want = np.stack([fv.decrypt(s.octx, kr["s"], rnd[i]) for i in range(2)])
+    assert np.array_equal(got, want), "decrypt random"
+    s.ctx.close()
+
+
+def check_scalar_mac(backend, n, k, seed_id=1):
+    s = Setup(backend, n, k, seed_id=seed_id, with_keys=False)
+    n_in = 9
+    cts = gen.uniform_residues(s.rng, s.q, n, lead=(n_in, 2))
+    for l, p in enumerate(s.q):                      # extreme residues
+        cts[0, 0, l, :8] = p - 1
+        cts[1, 1, l, :8] = 0
+    dcts = backend.dev(cts)
+
+    def run(idx, w, bound):
+        out = backend.host(s.ctx.ct_scalar_mac(dcts, backend.dev(idx), backend.dev(w), bound))
+        G, F, T = w.shape
+        assert out.shape == (F, G, 2, k, n)
+        for g in range(G):
+            for f in range(F):
+                assert np.array_equal(out[f, g], fv.scalar_mac(s.octx, cts, idx[g], w[g, f])), ("mac", g, f)
+
+    # small weights, several filters, repeated indices, ragged group count
+    idx = s.rng.integers(0, n_in, size=(3, 7)).astype(np.uint32)
+    run(idx, gen.int_weights(s.rng, (3, 5, 7), 15), 15)
+    # T = 1, F = 1 and F = 16
+    run(idx[:, :1].copy(), gen.int_weights(s.rng, (3, 1, 1), 8), 8)
+    run(idx[:1].copy(), gen.int_weights(s.rng, (1, 16, 7), 31), 31)
+    # extreme weights force intermediate reductions of the partial sums (4 terms per reduction)
+    big = 2 ** 31 - 1
+    w = gen.int_weights(s.rng, (2, 2, 7), big)
+    w[0, 0, :] = big
+    w[0, 1, :] = -big
+    run(idx[:2].copy(), w, big)
+    # all-zero weights and bound 0
+    run(idx[:1].copy(), np.zeros((1, 2, 7), dtype=np.int32), 0)
+    assert s.ctx.bad_inputs() == 0
+    # out-of-range index / weight beyond the bound are skipped and counted, without faulting
+    bad_idx = idx[:1].copy()
+    bad_idx[0, 2] = n_in + 5
+    w1 = gen.int_weights(s.rng, (1, 1, 7), 3)
+    out = backend.host(s.ctx.ct_scalar_mac(dcts, backend.dev(bad_idx), backend.dev(w1), 3))
+    keep = [j for j in range(7) if j != 2]
+    assert np.array_equal(out[0, 0], fv.scalar_mac(s.octx, cts, bad_idx[0, keep], w1[0, 0, keep]))
+    assert s.ctx.bad_inputs() == 1
+    w1[0, 0, 4] = 99
+    out = backend.host(s.ctx.ct_scalar_mac(dcts, backend.dev(idx[:1].copy()), backend.dev(w1), 3))
+    keep = [j for j in range(7) if j != 4]
+    assert np.array_equal(out[0, 0], fv.scalar_mac(s.octx, cts, idx[0, keep], w1[0, 0, keep]))
+    assert s.ctx.bad_inputs() == 2
+    s.ctx.close()
+
+
+def check_mac_linear_in_ntt_domain(backend, n, k, seed_id=1):
+    """MAC of transformed inputs equals the transform of the MAC."""
+    s = Setup(backend, n, k, seed_id=seed_id, with_keys=False)
+    cts = gen.uniform_residues(s.rng, s.q, n, lead=(4, 2))
+    idx = np.array([[0, 1, 2, 3]], dtype=np.uint32)
+    w = gen.int_weights(s.rng, (1, 2, 4), 15)
+    a = s.ctx.ct_scalar_mac(backend.dev(cts), backend.dev(idx), backend.dev(w), 15)
+    s.ctx.ntt_fwd(a)
+    hat = backend.dev(cts)
+    s.ctx.ntt_fwd(hat)
+    b = s.ctx.ct_scalar_mac(hat, backend.dev(idx), backend.dev(w), 15)
+    assert np.array_equal(backend.host(a), backend.host(b))
+    s.ctx.close()
+
+
+def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=None, force_exact=False,
+                       check_decrypt=True):
+    s = Setup(backend, n, k, seed_id=seed_id)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    slots, polys, er, gcts = s.encrypt_oracle(n_genuine)
+    rnd = gen.uniform_residues(s.rng, s.q, n, lead=(n_random, 2))
+    # centred-lift corner cases: residues of 0, +-1 and +-(q-1)/2 in the first coefficients
+    Q = s.octx.Q
+    for pos, val in enumerate((0, 1, -1, (Q - 1) // 2, -((Q - 1) // 2))):
+        for l, p in enumerate(s.q):
+            rnd[0, 0, l, pos] = val % p
+            rnd[0, 1, l, pos] = (-val) % p
+    cts = np.concatenate([gcts, rnd]) if n_genuine else rnd
+    if chunk:
+        s.ctx.set_square_chunk(chunk)
+    if force_exact:
+        s.ctx.set_ambiguity_band(2 ** 64 - 1)
+    out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
+    want = np.stack([fv.square_relin(s.octx, cts[i], s.evk) for i in range(len(cts))])
+    assert np.array_equal(out, want), ("square_relin", n, k)
+    if force_exact:
+        assert s.ctx.exact_fallbacks() > n          # the exact comparison really ran
+    if check_decrypt and n_genuine:
+        m2 = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[0]), n, s.t)
+        assert np.array_equal(m2, (slots[0].astype(np.uint64) ** 2 % s.t).astype(np.uint32))
+    # in place
+    buf = backend.dev(cts)
+    s.ctx.ct_square_relin(buf, out=buf)
+    assert np.array_equal(backend.host(buf), want), "square_relin in place"
+    s.ctx.close()
+
+
+def check_conv_layer_small(backend, seed_id=1):
+    """A small convolution + square layer end to end: 1x6x6 image, 2 filters 3x3 stride 2 (+ one padded)."""
+    n, k = 1024, 3
+    s = Setup(backend, n, k, seed_id=seed_id, stream=7)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    c_in, h, w_, F, fh, fw, stride = 1, 6, 6, 2, 3, 3, 2
+    slots, polys, er, cts = s.encrypt_oracle(c_in * h * w_, high=4)
+    weights = gen.int_weights(s.rng, (F, c_in, fh, fw), 3)
+    idx, valid, (ho, wo) = layers.conv_index_table(c_in, h, w_, fh, fw, stride)
+    wt = layers.conv_weight_table(weights, idx.shape[0])
+    mac = s.ctx.ct_scalar_mac(backend.dev(cts), backend.dev(idx), backend.dev(wt), 3)
+    sq = backend.host(s.ctx.ct_square_relin(mac.reshape((F * ho * wo, 2, k, n))))
+    # plain convolution on the slot values, written directly from the layer definition
+    img = slots.astype(np.int64).reshape(c_in, h, w_, n)
+    for f in range(F):
+        for j in range(ho):
+            for kk in range(wo):
+                acc = np.zeros(n, dtype=np.int64)
+                for c in range(c_in):
+                    for dy in range(fh):
+                        for dx in range(fw):
+                            acc += int(weights[f, c, dy, dx]) * img[c, j * stride + dy, kk * stride + dx]
+                want = (acc % s.t) ** 2 % s.t
+                o = f * ho * wo + j * wo + kk
+                got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], sq[o]), n, s.t)
+                assert np.array_equal(got.astype(np.int64), want), ("conv+square", f, j, kk)
+    s.ctx.close()

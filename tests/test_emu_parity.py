@@ -1,0 +1,68 @@
+"""Kernel sources checked on the CPU: the library compiled with -DHCNN_HOSTEMU runs the same
+kernel phase bodies and host orchestration as loops, and must match the oracle bit for bit.
+(The product path itself is tested in test_gpu_parity.py; nothing here touches a GPU.)"""
+import numpy as np
+import pytest
+
+import emu
+import parity_cases as pc
+
+
+class EmuBackend:
+    def __init__(self):
+        self.lib = emu.lib()
+
+    def make_ctx(self, n, q, p, t):
+        return emu.EmuContext(n, q, p, t)
+
+    @staticmethod
+    def dev(a):
+        return emu.aligned(np.ascontiguousarray(a))
+
+    @staticmethod
+    def host(buf):
+        return buf
+
+
+@pytest.fixture(scope="module")
+def backend():
+    return EmuBackend()
+
+
+@pytest.mark.parametrize("n,k,n_polys,rows", [(1024, 2, 3, None), (2048, 3, 2, 3), (4096, 2, 1, 2),
+                                             (8192, 2, 1, 1), (16384, 1, 1, 1), (32768, 1, 1, 1)])
+def test_ntt_all_sizes(backend, n, k, n_polys, rows):
+    pc.check_ntt(backend, n, k, n_polys, rows)
+
+
+@pytest.mark.parametrize("n,k", [(1024, 2), (2048, 3)])
+def test_keygen_encrypt_decrypt(backend, n, k):
+    pc.check_keygen_encrypt_decrypt(backend, n, k)
+
+
+@pytest.mark.parametrize("n,k", [(1024, 2), (2048, 5)])
+def test_scalar_mac(backend, n, k):
+    pc.check_scalar_mac(backend, n, k)
+    pc.check_mac_linear_in_ntt_domain(backend, n, k)
+
+
+def test_square_relin_tiny_config(backend):
+    pc.check_square_relin(backend, 1024, 2)
+
+
+def test_square_relin_chunked_ragged(backend):
+    pc.check_square_relin(backend, 1024, 3, n_random=4, n_genuine=1, chunk=2)
+
+
+def test_square_relin_exact_comparison_path(backend):
+    pc.check_square_relin(backend, 1024, 2, force_exact=True)
+    pc.check_square_relin(backend, 2048, 4, n_random=1, n_genuine=1, force_exact=True)
+
+
+def test_square_relin_more_than_16_limbs(backend):
+    # k = 17 > 16 exercises the intermediate reductions of the 64-bit inner products
+    pc.check_square_relin(backend, 1024, 17, n_random=1, n_genuine=1)
+
+
+def test_conv_square_layer(backend):
+    pc.check_conv_layer_small(backend)

@@ -1,0 +1,70 @@
+"""Index tables for convolution-type layers: counts printed in the paper and the layer definition."""
+import os
+
+import numpy as np
+
+from paper_1811_00778_amd import layers
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden(name):
+    out = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        if line.strip() and not line.startswith("#"):
+            key, *vals = line.split()
+            out[key] = vals
+    return out
+
+
+def test_mnist_layer_counts_match_paper_table():
+    g = _golden("mnist_layer_counts.txt")
+    idx, valid, (ho, wo) = layers.conv_index_table(1, 28, 28, 5, 5, 2)
+    F = 5
+    assert 28 * 28 == int(g["layer1_inputs"][0])
+    assert F * ho * wo == int(g["layer1_outputs"][0]) == int(g["layer2_hsquare"][0])
+    assert F * idx.size == int(g["layer1_hmultplain"][0])
+    assert valid.all() and idx.max() == 26 * 28 + 26     # 12 placements of stride 2 reach row and column 26
+    idx3, _, (h3, w3) = layers.conv_index_table(5, 12, 12, 5, 5, 2)
+    assert 50 * h3 * w3 == int(g["layer3_outputs"][0])
+    # per output neuron the paper counts one filter plane (25 products), not 5 channels x 25
+    assert 50 * h3 * w3 * 25 == int(g["layer3_hmultplain"][0])
+    assert 10 * 800 == int(g["layer5_hmultplain"][0])
+    total = int(g["layer1_hmultplain"][0]) + int(g["layer3_hmultplain"][0]) + int(g["layer5_hmultplain"][0])
+    assert total == int(g["total_hmultplain"][0])
+    assert 720 + 800 == int(g["total_hsquare"][0])
+
+
+def test_ciphertext_size_formula():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "ciphertext_size.txt")) if l[0] not in "#\n"]
+    for case, N, logq, nbytes in rows[1:]:
+        assert 2 * int(N) * int(logq) // 8 == int(nbytes)
+    # this build: 30-bit primes in 32-bit words, [2][k][n] uint32
+    assert 2 * 8 * 8192 * 4 == 512 * 1024
+
+
+def test_conv_table_matches_direct_convolution():
+    rng = np.random.default_rng(3)
+    c_in, h, w, F, fh, fw, s, pad = 3, 9, 8, 4, 3, 3, 2, 1
+    x = rng.integers(0, 256, size=(c_in, h, w))
+    wt = rng.integers(-7, 8, size=(F, c_in, fh, fw))
+    idx, valid, (ho, wo) = layers.conv_index_table(c_in, h, w, fh, fw, s, pad)
+    wtab = layers.conv_weight_table(wt, idx.shape[0], valid)
+    flat = x.reshape(-1)
+    got = np.einsum("gft,gt->fg", wtab, flat[idx]).reshape(F, ho, wo)
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad)))
+    for f in range(F):
+        for j in range(ho):
+            for k in range(wo):
+                assert got[f, j, k] == (wt[f] * xp[:, j * s:j * s + fh, k * s:k * s + fw]).sum()
+    # placement rule of the blocking section: top-left input index j*s*w + k*s (no padding)
+    idx0, _, (ho0, wo0) = layers.conv_index_table(1, h, w, fh, fw, s)
+    for j in range(ho0):
+        for k in range(wo0):
+            assert idx0[j * wo0 + k, 0] == j * s * w + k * s
+
+
+def test_fc_tables():
+    w = np.arange(30, dtype=np.int32).reshape(3, 10)
+    assert layers.fc_index_table(10).tolist() == [list(range(10))]
+    assert layers.fc_weight_table(w).shape == (1, 3, 10)
