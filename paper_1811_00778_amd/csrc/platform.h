@@ -50,6 +50,11 @@ inline int copy_h2d(void* d, const void* h, size_t bytes, hcnn_stream_t) { std::
 inline int copy_d2h(void* h, const void* d, size_t bytes, hcnn_stream_t) { std::memcpy(h, d, bytes); return 0; }
 inline int copy_d2d(void* d, const void* s, size_t bytes, hcnn_stream_t) { std::memmove(d, s, bytes); return 0; }
 inline int stream_sync(hcnn_stream_t) { return 0; }
+typedef int hcnn_event_t;
+inline int event_create(hcnn_event_t* e) { *e = 0; return 0; }
+inline int event_destroy(hcnn_event_t) { return 0; }
+inline int event_record(hcnn_event_t, hcnn_stream_t) { return 0; }
+inline int event_elapsed_ms(float* ms, hcnn_event_t, hcnn_event_t) { *ms = 0.f; return 0; }
 inline size_t max_lds_bytes() { return 160 * 1024; }
 HCNN_HD void atomic_inc64(unsigned long long* p) { *p += 1; }
 
@@ -90,6 +95,11 @@ inline int copy_d2d(void* d, const void* s_, size_t bytes, hcnn_stream_t s) {
   return (int)hipMemcpyAsync(d, s_, bytes, hipMemcpyDeviceToDevice, s);
 }
 inline int stream_sync(hcnn_stream_t s) { return (int)hipStreamSynchronize(s); }
+typedef hipEvent_t hcnn_event_t;
+inline int event_create(hcnn_event_t* e) { return (int)hipEventCreate(e); }
+inline int event_destroy(hcnn_event_t e) { return (int)hipEventDestroy(e); }
+inline int event_record(hcnn_event_t e, hcnn_stream_t s) { return (int)hipEventRecord(e, s); }
+inline int event_elapsed_ms(float* ms, hcnn_event_t a, hcnn_event_t b) { return (int)hipEventElapsedTime(ms, a, b); }
 inline size_t max_lds_bytes() {
   int dev = 0, v = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;

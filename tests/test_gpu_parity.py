@@ -1,0 +1,183 @@
+"""Parity of the HIP path with the CPU oracle on a real MI355X, through the C ABI
+(torch only allocates the device buffers).  Bit-exact: all of it is integer work."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+import parity_cases as pc
+from oracle import fv
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[gpu-parity] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+class GpuBackend:
+    def __init__(self):
+        from paper_1811_00778_amd import binding
+        self.binding = binding
+        self.lib = binding.lib()
+        self._ctx = None
+
+    def make_ctx(self, n, q, p, t):
+        self._ctx = self.binding.Context(n, q, p, t)
+        return self._ctx
+
+    def dev(self, a):
+        return self._ctx.to_device(np.ascontiguousarray(a))
+
+    def host(self, buf):
+        return self._ctx.to_host_u32(buf)
+
+
+@pytest.fixture(scope="module")
+def backend():
+    return GpuBackend()
+
+
+@pytest.mark.parametrize("n,k,n_polys,rows", [(1024, 2, 16, None), (2048, 3, 5, 4), (4096, 2, 3, 2),
+                                             (8192, 8, 7, 3), (16384, 3, 2, 2), (32768, 2, 2, 1)])
+def test_ntt_all_sizes(backend, n, k, n_polys, rows):
+    say("ntt n=%d k=%d polys=%d" % (n, k, n_polys))
+    pc.check_ntt(backend, n, k, n_polys, rows)
+
+
+@pytest.mark.parametrize("n,k", [(1024, 2), (2048, 3)])
+def test_keygen_encrypt_decrypt(backend, n, k):
+    say("keygen/encrypt/decrypt n=%d k=%d" % (n, k))
+    pc.check_keygen_encrypt_decrypt(backend, n, k)
+
+
+@pytest.mark.parametrize("n,k", [(1024, 2), (2048, 5)])
+def test_scalar_mac(backend, n, k):
+    say("scalar_mac n=%d k=%d" % (n, k))
+    pc.check_scalar_mac(backend, n, k)
+    pc.check_mac_linear_in_ntt_domain(backend, n, k)
+
+
+def test_square_relin_tiny_config(backend):
+    say("square_relin n=1024 k=2")
+    pc.check_square_relin(backend, 1024, 2)
+
+
+def test_square_relin_chunked_ragged(backend):
+    say("square_relin chunked n=1024 k=3")
+    pc.check_square_relin(backend, 1024, 3, n_random=4, n_genuine=1, chunk=2)
+
+
+def test_square_relin_exact_comparison_path(backend):
+    say("square_relin forced exact comparison")
+    pc.check_square_relin(backend, 1024, 2, force_exact=True)
+    pc.check_square_relin(backend, 2048, 4, n_random=1, n_genuine=1, force_exact=True)
+
+
+def test_square_relin_more_than_16_limbs(backend):
+    say("square_relin k=17")
+    pc.check_square_relin(backend, 1024, 17, n_random=1, n_genuine=1)
+
+
+def test_conv_square_layer(backend):
+    say("conv + square small layer")
+    pc.check_conv_layer_small(backend)
+
+
+def test_empty_batches_are_noops(backend):
+    s = pc.Setup(backend, 1024, 2)
+    ctx = s.ctx
+    ctx.set_relin_key(backend.dev(s.evk))
+    import torch
+    empty = torch.empty((0, 2, 2, 1024), dtype=torch.int32, device=ctx.device)
+    assert ctx.ct_square_relin(empty).shape[0] == 0
+    ctx.ntt_fwd(torch.empty((0, 2, 1024), dtype=torch.int32, device=ctx.device))
+    ctx.close()
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _oracle_rows_check(name, got_row, want_row):
+    assert np.array_equal(got_row, want_row), name
+
+
+def test_config2_full_batch_ntt_and_squarings(backend):
+    """n=8192, 8 primes, 64 random ciphertexts: transforms on the whole batch (sampled rows against the
+    oracle, round trip on everything), 64 squarings in one call (sampled ciphertexts against the oracle)."""
+    cfg = gen.CONFIGS[2]
+    n, k = cfg["n"], cfg["k"]
+    say("config 2: setup")
+    s = pc.Setup(backend, n, k, seed_id=2)
+    cts = gen.uniform_residues(s.rng, s.q, n, lead=(cfg["n_ct"], 2))
+    buf = backend.dev(cts)
+    s.ctx.ntt_fwd(buf)
+    hat = backend.host(buf).copy()
+    for (i, b, l) in [(0, 0, 0), (17, 1, 3), (63, 1, 7)]:
+        say("config 2: oracle NTT row %s" % ((i, b, l),))
+        assert np.array_equal(hat[i, b, l], fv.ntt_forward(cts[i, b, l], s.q[l]))
+    s.ctx.ntt_inv(buf)
+    assert np.array_equal(backend.host(buf), cts)
+    say("config 2: 64 squarings on the GPU")
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
+    for i in (5, 63):
+        t0 = time.time()
+        want = fv.square_relin(s.octx, cts[i], s.evk)
+        say("config 2: oracle squaring of ciphertext %d took %.1f s" % (i, time.time() - t0))
+        assert np.array_equal(out[i], want)
+    assert s.ctx.exact_fallbacks() == 0
+    s.ctx.close()
+
+
+def test_config3_mnist_conv_layer(backend):
+    """n=8192, 8 primes: 784 genuinely encrypted pixel ciphertexts (values 0..255 in 8192 slots), 5 filters
+    5x5 stride 2 -> 720 outputs by scalar MAC, then 720 squarings.  Sampled outputs against the oracle,
+    and the decrypted result against the plain convolution squared."""
+    from paper_1811_00778_amd import layers
+    cfg = gen.CONFIGS[3]
+    n, k, t = cfg["n"], cfg["k"], cfg["t"]
+    cv = cfg["conv"]
+    say("config 3: setup")
+    s = pc.Setup(backend, n, k, seed_id=3)
+    n_in = cv["c_in"] * cv["h"] * cv["w"]
+    slots = gen.slot_values(s.rng, n_in, n, 256)
+    er = gen.encryption_randomness(s.rng, n, n_in)
+    say("config 3: slot encoding of 784 images planes (oracle side)")
+    polys = np.stack([fv.slot_encode(slots[i], n, t) for i in range(n_in)])
+    say("config 3: GPU encryption of 784 ciphertexts")
+    dcts = s.ctx.encrypt(backend.dev(s.pk), backend.dev(polys), backend.dev(er["u"]), backend.dev(er["e1"]),
+                         backend.dev(er["e2"]))
+    cts = backend.host(dcts)
+    for i in (0, 500):
+        say("config 3: oracle encryption %d" % i)
+        assert np.array_equal(cts[i], fv.encrypt(s.octx, s.pk, polys[i], er["u"][i], er["e1"][i], er["e2"][i]))
+    weights = gen.int_weights(s.rng, (cv["filters"], cv["c_in"], cv["fh"], cv["fw"]), cv["w_bound"])
+    idx, valid, (ho, wo) = layers.conv_index_table(cv["c_in"], cv["h"], cv["w"], cv["fh"], cv["fw"], cv["stride"])
+    wt = layers.conv_weight_table(weights, idx.shape[0])
+    say("config 3: scalar MAC 784 -> 720")
+    mac = s.ctx.ct_scalar_mac(dcts, backend.dev(idx), backend.dev(wt), cv["w_bound"])
+    F, G = cv["filters"], ho * wo
+    assert F * G == cfg["n_square"]
+    hmac = backend.host(mac)
+    for (f, g) in [(0, 0), (1, 77), (2, 143), (4, 100), (3, 12), (4, 143)]:
+        assert np.array_equal(hmac[f, g], fv.scalar_mac(s.octx, cts, idx[g], wt[g, f])), ("mac", f, g)
+    say("config 3: 720 squarings")
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    sq = backend.host(s.ctx.ct_square_relin(mac.reshape((F * G, 2, k, n))))
+    o = 2 * G + 143
+    t0 = time.time()
+    want = fv.square_relin(s.octx, hmac[2, 143], s.evk)
+    say("config 3: oracle squaring took %.1f s" % (time.time() - t0))
+    assert np.array_equal(sq[o], want)
+    img = slots.astype(np.int64).reshape(cv["c_in"], cv["h"], cv["w"], n)
+    for (f, j, kk) in [(0, 0, 0), (4, 11, 11)]:
+        acc = np.zeros(n, dtype=np.int64)
+        for c in range(cv["c_in"]):
+            for dy in range(cv["fh"]):
+                for dx in range(cv["fw"]):
+                    acc += int(weights[f, c, dy, dx]) * img[c, j * cv["stride"] + dy, kk * cv["stride"] + dx]
+        got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], sq[f * G + j * wo + kk]), n, t)
+        assert np.array_equal(got.astype(np.int64), (acc % t) ** 2 % t), ("conv^2", f, j, kk)
+    s.ctx.close()
