@@ -181,3 +181,123 @@ def test_config3_mnist_conv_layer(backend):
         got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], sq[f * G + j * wo + kk]), n, t)
         assert np.array_equal(got.astype(np.int64), (acc % t) ** 2 % t), ("conv^2", f, j, kk)
     s.ctx.close()
+
+
+def _gpu_encrypt_random_plaintexts(backend, s, count, batch=256):
+    """`count` genuine encryptions of uniformly drawn plaintext polynomials (coefficients in [0,t)),
+    made on the GPU in batches; returns (device ciphertexts, host plaintext polynomials, randomness)."""
+    import torch
+    n = s.n
+    polys = s.rng.integers(0, s.t, size=(count, n), dtype=np.int64).astype(np.uint32)
+    er = gen.encryption_randomness(s.rng, n, count)
+    out = torch.empty((count, 2, s.k, n), dtype=torch.int32, device=s.ctx.device)
+    dpk = backend.dev(s.pk)
+    for c0 in range(0, count, batch):
+        sl = slice(c0, min(count, c0 + batch))
+        out[sl] = s.ctx.encrypt(dpk, backend.dev(polys[sl]), backend.dev(er["u"][sl]), backend.dev(er["e1"][sl]),
+                                backend.dev(er["e2"][sl]))
+    return out, polys, er
+
+
+def test_config4_cifar_conv_layer(backend):
+    """n=16384, 16 primes: 3072 encrypted inputs, 8 filters 3x3x3 stride 2 -> 1800 outputs, 1800 squarings.
+    Sampled MAC outputs and one whole squaring against the oracle; the decrypted result of another output
+    against the plain convolution squared."""
+    from paper_1811_00778_amd import layers
+    cfg = gen.CONFIGS[4]
+    n, k, t = cfg["n"], cfg["k"], cfg["t"]
+    cv = cfg["conv"]
+    say("config 4: setup (k_aux follows from t*n*q)")
+    s = pc.Setup(backend, n, k, seed_id=4)
+    assert len(s.p) == k + 2
+    n_in = cv["c_in"] * cv["h"] * cv["w"]
+    say("config 4: GPU encryption of %d ciphertexts" % n_in)
+    dcts, polys, er = _gpu_encrypt_random_plaintexts(backend, s, n_in)
+    i = 1234
+    t0 = time.time()
+    want = fv.encrypt(s.octx, s.pk, polys[i], er["u"][i], er["e1"][i], er["e2"][i])
+    say("config 4: oracle encryption took %.1f s" % (time.time() - t0))
+    assert np.array_equal(backend.host(dcts[i]), want)
+    weights = gen.int_weights(s.rng, (cv["filters"], cv["c_in"], cv["fh"], cv["fw"]), cv["w_bound"])
+    idx, valid, (ho, wo) = layers.conv_index_table(cv["c_in"], cv["h"], cv["w"], cv["fh"], cv["fw"], cv["stride"])
+    wt = layers.conv_weight_table(weights, idx.shape[0])
+    F, G = cv["filters"], ho * wo
+    assert F * G == cfg["n_square"] and idx.shape[1] == 27
+    say("config 4: scalar MAC %d -> %d" % (n_in, F * G))
+    mac = s.ctx.ct_scalar_mac(dcts, backend.dev(idx), backend.dev(wt), cv["w_bound"])
+    for (f, g) in [(0, 0), (7, G - 1), (3, 100)]:
+        need = sorted(set(int(v) for v in idx[g]))
+        sub = {v: backend.host(dcts[v]) for v in need}
+        local = np.stack([sub[int(v)] for v in idx[g]])
+        want = fv.scalar_mac(s.octx, local, list(range(len(idx[g]))), wt[g, f])
+        assert np.array_equal(backend.host(mac[f, g]), want), ("mac", f, g)
+    say("config 4: %d squarings" % (F * G))
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    flat = mac.reshape((F * G, 2, k, n))
+    sq = s.ctx.ct_square_relin(flat)
+    assert s.ctx.exact_fallbacks() == 0
+    # decrypted output (f, j, kk) against the plain layer on the slot values of its 27 inputs
+    f, j, kk = 5, 7, 9
+    g = j * wo + kk
+    slots = {int(v): fv.slot_decode(polys[int(v)], n, t).astype(np.int64) for v in idx[g]}
+    acc = np.zeros(n, dtype=np.int64)
+    for tau, v in enumerate(idx[g]):
+        acc += int(wt[g, f, tau]) * slots[int(v)]
+    t0 = time.time()
+    got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], backend.host(sq[f * G + g])), n, t)
+    say("config 4: oracle decryption took %.1f s" % (time.time() - t0))
+    assert np.array_equal(got.astype(np.int64), (acc % t) ** 2 % t)
+    # one whole squaring, residue for residue
+    o = 2 * G + 17
+    t0 = time.time()
+    want = fv.square_relin(s.octx, backend.host(flat[o]), s.evk)
+    say("config 4: oracle squaring took %.1f s" % (time.time() - t0))
+    assert np.array_equal(backend.host(sq[o]), want)
+    s.ctx.close()
+
+
+def test_config5_deep_modulus(backend):
+    """n=32768, 24 primes (26 auxiliary): 32 squarings with relinearisation and a 1024 -> 10 scalar MAC.
+    A whole squaring costs the oracle minutes here, so the squaring is checked through decryption
+    (oracle decrypt of the GPU result equals the slot-wise square); the MAC is compared residue for residue."""
+    import torch
+    from paper_1811_00778_amd import layers
+    cfg = gen.CONFIGS[5]
+    n, k, t = cfg["n"], cfg["k"], cfg["t"]
+    say("config 5: setup")
+    s = pc.Setup(backend, n, k, seed_id=5)
+    assert len(s.p) == k + 2
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    say("config 5: inputs (2 genuine + 30 random ciphertexts)")
+    dgen, polys, er = _gpu_encrypt_random_plaintexts(backend, s, 2)
+    t0 = time.time()
+    want = fv.encrypt(s.octx, s.pk, polys[1], er["u"][1], er["e1"][1], er["e2"][1])
+    say("config 5: oracle encryption took %.1f s" % (time.time() - t0))
+    assert np.array_equal(backend.host(dgen[1]), want)
+    rnd = gen.uniform_residues(s.rng, s.q, n, lead=(30, 2))
+    batch = torch.cat([dgen, backend.dev(rnd)])
+    say("config 5: 32 squarings")
+    sq = s.ctx.ct_square_relin(batch)
+    assert s.ctx.exact_fallbacks() == 0
+    t0 = time.time()
+    got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], backend.host(sq[1])), n, t)
+    say("config 5: oracle decryption took %.1f s" % (time.time() - t0))
+    m = fv.slot_decode(polys[1], n, t).astype(np.uint64)
+    assert np.array_equal(got, (m * m % t).astype(np.uint32))
+    # determinism across chunkings of the batch: same residues when squared four at a time
+    s.ctx.set_square_chunk(4)
+    sq4 = s.ctx.ct_square_relin(batch)
+    assert torch.equal(sq, sq4)
+    del sq4, batch, sq
+    say("config 5: fully connected MAC 1024 -> 10")
+    fc = cfg["fc"]
+    cts = gen.uniform_residues(s.rng, s.q, n, lead=(fc["n_in"], 2))
+    w = gen.int_weights(s.rng, (fc["n_out"], fc["n_in"]), fc["w_bound"])
+    out = s.ctx.ct_scalar_mac(backend.dev(cts), backend.dev(layers.fc_index_table(fc["n_in"])),
+                              backend.dev(layers.fc_weight_table(w)), fc["w_bound"])
+    for o in (0, 9):
+        t0 = time.time()
+        want = fv.scalar_mac(s.octx, cts, list(range(fc["n_in"])), w[o])
+        say("config 5: oracle MAC output %d took %.1f s" % (o, time.time() - t0))
+        assert np.array_equal(backend.host(out[o, 0]), want)
+    s.ctx.close()
