@@ -154,8 +154,7 @@ struct BConvHost {
   uint32_t ks = 0, kd = 0;
   std::vector<Mod> src_mod, dst_mod;
   std::vector<ShoupConst> zmul, xmul;
-  std::vector<uint64_t> fix;
-  std::vector<uint32_t> ginv, half, B, Mmod;
+  std::vector<uint32_t> ginv, half, Bp, Vp;
 };
 
 struct hcnn_ctx {
@@ -169,7 +168,7 @@ struct hcnn_ctx {
   ShoupConst* d_tw_fwd = nullptr;   // [k + kp][n]
   ShoupConst* d_tw_inv = nullptr;
   ShoupConst* d_delta = nullptr;    // [k] floor(q/t) mod q_l
-  ShoupConst* d_tq_inv = nullptr;   // [kp]
+  uint32_t* d_tq_inv = nullptr;     // [kp] t * q^-1 mod p_j
   BConvDev ext{}, to_p{}, to_q{}, dec{};
   uint32_t neg_qinv_t = 0;
   unsigned long long* d_counters = nullptr;   // [2]
@@ -180,7 +179,7 @@ struct hcnn_ctx {
   uint32_t* scratch = nullptr;
   size_t scratch_bytes = 0;
 
-  uint64_t band = 256;
+  uint32_t band = 128;
   uint64_t square_chunk = 0;
   size_t max_lds = 0;
 
@@ -214,6 +213,8 @@ template <class K> struct KernelClass { static constexpr int id = HCNN_PROF_OTHE
 template <int A, int B> struct KernelClass<NttFwd<A, B>> { static constexpr int id = HCNN_PROF_NTT_FWD; };
 template <int A, int B> struct KernelClass<NttInv<A, B>> { static constexpr int id = HCNN_PROF_NTT_INV; };
 template <> struct KernelClass<ExtKernel> { static constexpr int id = HCNN_PROF_BASE_EXT; };
+template <int A, int B> struct KernelClass<ExtKernelT<A, B>> { static constexpr int id = HCNN_PROF_BASE_EXT; };
+template <int A, int B> struct KernelClass<ScaleKernelT<A, B>> { static constexpr int id = HCNN_PROF_SCALE; };
 template <> struct KernelClass<TensorSqKernel> { static constexpr int id = HCNN_PROF_TENSOR; };
 template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
 template <> struct KernelClass<DigitKernel> { static constexpr int id = HCNN_PROF_DIGIT; };
@@ -266,7 +267,8 @@ int fold_profile(hcnn_ctx* c) {
 
 // Tables of an exact centred base conversion src -> dst.
 //   zfac[i]   extra factor folded into z_i (1 or t), also used as xmul
-//   fold_inv  when true, B and Mmod carry the factor M^-1 (B = m_i^-1 mod m'_j, Mmod = 1)
+//   fold_inv  when true the tables give -(x * M^-1): Bp = m'_j - m_i^-1, Vp = 1
+//             otherwise they give x:                 Bp = M/m_i mod m'_j, Vp = m'_j - M mod m'_j
 BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_t>& dst, uint32_t zfac,
                      bool fold_inv, bool dst_is_rns_prime) {
   BConvHost h;
@@ -278,7 +280,6 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
     const uint32_t Mi_inv = h_inv(h_prod_mod(src, (int)i, m), m);        // (M/m_i)^-1 mod m_i
     h.zmul.push_back(h_shoup(h_mulmod(Mi_inv, zfac % m, m), m));
     h.xmul.push_back(h_shoup(zfac % m, m));
-    h.fix.push_back((uint64_t)((((u128)1) << 93) / m));
   }
   h.ginv.assign((size_t)h.ks * h.ks, 0);
   for (uint32_t i = 0; i < h.ks; ++i)
@@ -294,34 +295,33 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
     }
     h.half[i] = tt;
   }
-  h.B.assign((size_t)h.ks * h.kd, 0);
-  h.Mmod.assign(h.kd, 0);
+  h.Bp.assign((size_t)h.ks * h.kd, 0);
+  h.Vp.assign(h.kd, 0);
   for (uint32_t j = 0; j < h.kd; ++j) {
     const uint32_t mj = dst[j];
     if (dst_is_rns_prime) h.dst_mod.push_back(h_mod(mj));
     else { Mod dm{}; dm.p = mj; h.dst_mod.push_back(dm); }
     for (uint32_t i = 0; i < h.ks; ++i)
-      h.B[(size_t)i * h.kd + j] = fold_inv ? h_inv(src[i] % mj, mj) : h_prod_mod(src, (int)i, mj);
-    h.Mmod[j] = fold_inv ? 1u : h_prod_mod(src, -1, mj);
+      h.Bp[(size_t)i * h.kd + j] = fold_inv ? mj - h_inv(src[i] % mj, mj) : h_prod_mod(src, (int)i, mj);
+    h.Vp[j] = fold_inv ? 1u : (mj - h_prod_mod(src, -1, mj)) % mj;
   }
   return h;
 }
 
 int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
   int e;
-  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint64_t* fx; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* Mm;
+  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* Mm;
   if ((e = upload(c, h.src_mod, &sm))) return e;
   if ((e = upload(c, h.dst_mod, &dm))) return e;
   if ((e = upload(c, h.zmul, &zm))) return e;
   if ((e = upload(c, h.xmul, &xm))) return e;
-  if ((e = upload(c, h.fix, &fx))) return e;
   if ((e = upload(c, h.ginv, &gi))) return e;
   if ((e = upload(c, h.half, &hf))) return e;
-  if ((e = upload(c, h.B, &B))) return e;
-  if ((e = upload(c, h.Mmod, &Mm))) return e;
+  if ((e = upload(c, h.Bp, &B))) return e;
+  if ((e = upload(c, h.Vp, &Mm))) return e;
   d->ks = h.ks; d->kd = h.kd;
-  d->src_mod = sm; d->dst_mod = dm; d->zmul = zm; d->xmul = xm; d->fix = fx;
-  d->ginv = gi; d->half = hf; d->B = B; d->Mmod = Mm;
+  d->src_mod = sm; d->dst_mod = dm; d->zmul = zm; d->xmul = xm;
+  d->ginv = gi; d->half = hf; d->Bp = B; d->Vp = Mm;
   return 0;
 }
 
@@ -384,10 +384,10 @@ int build_tables(hcnn_ctx* c) {
     if ((e = upload_bconv(c, h_ext, &c->ext))) return e;
     if ((e = upload_bconv(c, h_to_p, &c->to_p))) return e;
     if ((e = upload_bconv(c, h_to_q, &c->to_q))) return e;
-    std::vector<ShoupConst> tq;
+    std::vector<uint32_t> tq;
     for (uint32_t j = 0; j < c->kp; ++j) {
       const uint32_t pj = c->p[j];
-      tq.push_back(h_shoup(h_mulmod(c->t % pj, h_inv(h_prod_mod(c->q, -1, pj), pj), pj), pj));
+      tq.push_back(h_mulmod(c->t % pj, h_inv(h_prod_mod(c->q, -1, pj), pj), pj));
     }
     if ((e = upload(c, tq, &c->d_tq_inv))) return e;
   }
@@ -453,6 +453,26 @@ int ntt_dense(hcnn_ctx* c, const uint32_t* in, uint32_t* out, size_t rows, uint3
               uint32_t limb_base = 0) {
   NttRows r{in, out, rows, cycle, limb_base, cycle, 0, cycle, 0};
   return ntt_rows(c, r, inverse);
+}
+
+// Base-conversion kernels: register-resident variants for the basis sizes of the standard
+// parameter sets, the generic LDS-column kernels otherwise.
+int ext_dispatch(hcnn_ctx* c, size_t grid, const ExtArgs& a) {
+  const uint32_t k = c->k, kp = c->kp;
+#define HCNN_EXT_CASE(K, KP) \
+  if (k == K && kp == KP) return run<ExtKernelT<K, KP>>(c, grid, ExtKernelT<K, KP>::lds_bytes(), a);
+  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
+#undef HCNN_EXT_CASE
+  return run<ExtKernel>(c, grid, ExtKernel::lds_bytes(k), a);
+}
+
+int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
+  const uint32_t k = c->k, kp = c->kp;
+#define HCNN_SCALE_CASE(K, KP) \
+  if (k == K && kp == KP) return run<ScaleKernelT<K, KP>>(c, grid, ScaleKernelT<K, KP>::lds_bytes(), a);
+  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
+#undef HCNN_SCALE_CASE
+  return run<ScaleKernel>(c, grid, ScaleKernel::lds_bytes(k, kp), a);
 }
 
 template <int FT>
@@ -670,7 +690,7 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
     ExtArgs ea;
     ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
-    if ((e = run<ExtKernel>(c, cc * 2 * bpp, ExtKernel::lds_bytes(k), ea))) return e;
+    if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
     // 2. forward NTT over all k + k' limbs
     if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false))) return e;
     // 3. tensor: (c0^2, 2 c0 c1, c1^2)
@@ -683,7 +703,7 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
     ScaleArgs sa;
     sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
     sa.band = c->band; sa.fallback_counter = c->d_counters;
-    if ((e = run<ScaleKernel>(c, cc * 3 * bpp, need_lds_scale, sa))) return e;
+    if ((e = scale_dispatch(c, cc * 3 * bpp, sa))) return e;
     // 6. RNS digits of y2, each reduced modulo every q_j, then transformed
     DigitArgs da;
     da.y = y; da.dig = dig; da.mods = c->d_mods; da.k = k; da.n = n;
@@ -856,8 +876,9 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
   if (!c) return HCNN_ERR_NULL;
   switch (which) {
     case HCNN_OPT_AMBIGUITY_BAND:
-      if (value < 4ull * HCNN_MAX_LIMBS) return HCNN_ERR_ARG;   // never below the error bound of the estimate
-      c->band = value;
+      // never below the error bound 2*ks of the estimate, at most "always ask the exact comparison"
+      if (value < 4ull * HCNN_MAX_LIMBS || value > (1ull << 31)) return HCNN_ERR_ARG;
+      c->band = (uint32_t)value;
       return HCNN_OK;
     case HCNN_OPT_SQUARE_CHUNK:
       c->square_chunk = value;

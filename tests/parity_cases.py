@@ -162,11 +162,22 @@ def check_mac_linear_in_ntt_domain(backend, n, k, seed_id=1):
     s.ctx.close()
 
 
+def slot_prime_above(n, lower):
+    """Smallest prime t > lower with t = 1 (mod 2n) (a plaintext modulus that still supports slots)."""
+    t = lower - lower % (2 * n) + 2 * n + 1
+    while not fv.is_prime(t):
+        t += 2 * n
+    return t
+
+
 def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=None, force_exact=False,
-                       check_decrypt=True):
-    s = Setup(backend, n, k, seed_id=seed_id)
+                       check_decrypt=True, t=65537, expect_k_aux=None):
+    s = Setup(backend, n, k, t=t, seed_id=seed_id)
+    if expect_k_aux is not None:
+        assert len(s.p) == expect_k_aux
     s.ctx.set_relin_key(backend.dev(s.evk))
-    slots, polys, er, gcts = s.encrypt_oracle(n_genuine)
+    if n_genuine:
+        slots, polys, er, gcts = s.encrypt_oracle(n_genuine)
     rnd = gen.uniform_residues(s.rng, s.q, n, lead=(n_random, 2))
     # centred-lift corner cases: residues of 0, +-1 and +-(q-1)/2 in the first coefficients
     Q = s.octx.Q
@@ -178,7 +189,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
     if chunk:
         s.ctx.set_square_chunk(chunk)
     if force_exact:
-        s.ctx.set_ambiguity_band(2 ** 64 - 1)
+        s.ctx.set_ambiguity_band(2 ** 31)
     out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
     want = np.stack([fv.square_relin(s.octx, cts[i], s.evk) for i in range(len(cts))])
     assert np.array_equal(out, want), ("square_relin", n, k)

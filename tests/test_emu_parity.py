@@ -64,5 +64,14 @@ def test_square_relin_more_than_16_limbs(backend):
     pc.check_square_relin(backend, 1024, 17, n_random=1, n_genuine=1)
 
 
+@pytest.mark.parametrize("k,k_aux,big_t", [(8, 9, False), (16, 18, True), (24, 26, True)])
+def test_square_relin_register_variants_of_standard_bases(backend, k, k_aux, big_t):
+    # the basis sizes of the benchmark configurations, at a ring degree the oracle finishes quickly;
+    # a larger plaintext modulus makes k' = k + 2 necessary already at n = 1024
+    t = pc.slot_prime_above(1024, 1 << 22) if big_t else 65537
+    pc.check_square_relin(backend, 1024, k, n_random=1, n_genuine=1, t=t, expect_k_aux=k_aux)
+    pc.check_square_relin(backend, 1024, k, n_random=1, n_genuine=0, t=t, force_exact=True)
+
+
 def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
