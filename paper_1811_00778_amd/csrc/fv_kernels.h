@@ -474,8 +474,10 @@ struct MacArgs {
   uint32_t chunk;         // terms between reductions of the signed 64-bit accumulators
   unsigned long long* bad_counter;
 };
+// Fallback for gather rows too long to stage in LDS: indices and weights are read from global
+// memory inside the term loop.
 template <int FT>
-struct MacKernel {
+struct MacKernelDirect {
   static constexpr int kThreads = kEwThreads;
   static constexpr int kPhases = 1;
   struct Regs {};
@@ -486,12 +488,14 @@ struct MacKernel {
   }
   template <int PH>
   HCNN_HD static void phase(const MacArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
-    const size_t ct_words = (size_t)2 * a.k * a.n;
-    const uint32_t tiles = (uint32_t)(ct_words / (kThreads * kEwVec));
+    const uint32_t ct_words32 = 2u * a.k * a.n;                       // at most 2^22
+    const size_t ct_words = ct_words32;
+    const uint32_t tiles = ct_words32 / (kThreads * kEwVec);
     const uint32_t g = bid / tiles;
     const uint32_t tile = bid % tiles;
-    const size_t pos = ((size_t)tile * kThreads + tid) * kEwVec;     // word offset inside a ciphertext
-    const uint32_t limb = (uint32_t)((pos / a.n) % a.k);
+    const uint32_t pos = (tile * kThreads + tid) * kEwVec;            // word offset inside a ciphertext
+    const uint32_t row = tile / (a.n / (kThreads * kEwVec));          // (poly, limb) row; uniform in the block
+    const uint32_t limb = row % a.k;
     const Mod m = a.mods[limb];
     const uint32_t* idx = a.idx + (size_t)g * a.T;
     const int32_t* w = a.w + (size_t)g * a.F * a.T;
@@ -513,10 +517,11 @@ struct MacKernel {
           if (tid == 0 && tile == 0) atomic_inc64(a.bad_counter);
           wf = 0;
         }
-        s[f][0] += (int64_t)wf * (int64_t)x.x;
-        s[f][1] += (int64_t)wf * (int64_t)x.y;
-        s[f][2] += (int64_t)wf * (int64_t)x.z;
-        s[f][3] += (int64_t)wf * (int64_t)x.w;
+        // residues are below 2^30, so they are valid signed 32-bit operands: one 32x32+64 multiply-add each
+        s[f][0] += (int64_t)wf * (int64_t)(int32_t)x.x;
+        s[f][1] += (int64_t)wf * (int64_t)(int32_t)x.y;
+        s[f][2] += (int64_t)wf * (int64_t)(int32_t)x.z;
+        s[f][3] += (int64_t)wf * (int64_t)(int32_t)x.w;
       }
       if (++since == a.chunk) {
         since = 0;
@@ -531,6 +536,84 @@ struct MacKernel {
       r.x = (uint32_t)fold(s[f][0], m); r.y = (uint32_t)fold(s[f][1], m);
       r.z = (uint32_t)fold(s[f][2], m); r.w = (uint32_t)fold(s[f][3], m);
       *reinterpret_cast<U4*>(a.out + ((size_t)f * a.G + g) * ct_words + pos) = r;
+    }
+  }
+};
+
+// Main variant: the gather row and the F*T weights of the group are staged in LDS once per
+// workgroup (validated while staging: a bad index or weight becomes a zero-weight term on input 0),
+// so the term loop reads them with broadcast LDS reads and carries no branches.
+template <int FT>
+struct MacKernel {
+  static constexpr int kThreads = kEwThreads;
+  static constexpr int kPhases = 2;
+  struct Regs {};
+  static size_t lds_bytes(size_t F, size_t T) { return (1 + F) * T * 4; }
+  HCNN_HD static int64_t fold(int64_t s, const Mod& m) { return MacKernelDirect<FT>::fold(s, m); }
+  template <int PH>
+  HCNN_HD static void phase(const MacArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+    const uint32_t ct_words32 = 2u * a.k * a.n;                       // at most 2^22
+    const size_t ct_words = ct_words32;
+    const uint32_t tiles = ct_words32 / (kThreads * kEwVec);
+    const uint32_t g = bid / tiles;
+    const uint32_t tile = bid % tiles;
+    uint32_t* l_idx = lds;                                            // [T]
+    int32_t* l_w = reinterpret_cast<int32_t*>(lds + a.T);             // [F][T]
+    if constexpr (PH == 0) {
+      const uint32_t* idx = a.idx + (size_t)g * a.T;
+      const int32_t* w = a.w + (size_t)g * a.F * a.T;
+      for (uint32_t tau = tid; tau < a.T; tau += kThreads) {
+        uint32_t src = idx[tau];
+        const bool bad_src = src >= a.n_in;
+        if (bad_src) {
+          src = 0;
+          if (tile == 0) atomic_inc64(a.bad_counter);
+        }
+        l_idx[tau] = src;
+#pragma unroll
+        for (int f = 0; f < FT; ++f) {
+          int32_t wf = w[(size_t)f * a.T + tau];
+          if (wf > a.w_abs_max || wf < -a.w_abs_max) {
+            wf = 0;
+            if (tile == 0) atomic_inc64(a.bad_counter);
+          }
+          l_w[(size_t)f * a.T + tau] = bad_src ? 0 : wf;
+        }
+      }
+    } else {
+      const uint32_t pos = (tile * kThreads + tid) * kEwVec;          // word offset inside a ciphertext
+      const uint32_t row = tile / (a.n / (kThreads * kEwVec));        // (poly, limb) row; uniform in the block
+      const Mod m = a.mods[row % a.k];
+      const uint32_t* in = a.in + pos;
+      int64_t s[FT][4];
+#pragma unroll
+      for (int f = 0; f < FT; ++f) { s[f][0] = 0; s[f][1] = 0; s[f][2] = 0; s[f][3] = 0; }
+      uint32_t since = 0;
+      for (uint32_t tau = 0; tau < a.T; ++tau) {
+        const U4 x = *reinterpret_cast<const U4*>(in + (size_t)l_idx[tau] * ct_words);
+#pragma unroll
+        for (int f = 0; f < FT; ++f) {
+          const int32_t wf = l_w[(size_t)f * a.T + tau];
+          // residues are below 2^30, so they are valid signed 32-bit operands: one 32x32+64 multiply-add each
+          s[f][0] += (int64_t)wf * (int64_t)(int32_t)x.x;
+          s[f][1] += (int64_t)wf * (int64_t)(int32_t)x.y;
+          s[f][2] += (int64_t)wf * (int64_t)(int32_t)x.z;
+          s[f][3] += (int64_t)wf * (int64_t)(int32_t)x.w;
+        }
+        if (++since == a.chunk) {
+          since = 0;
+#pragma unroll
+          for (int f = 0; f < FT; ++f)
+            for (int q = 0; q < 4; ++q) s[f][q] = fold(s[f][q], m);
+        }
+      }
+#pragma unroll
+      for (int f = 0; f < FT; ++f) {
+        U4 r;
+        r.x = (uint32_t)fold(s[f][0], m); r.y = (uint32_t)fold(s[f][1], m);
+        r.z = (uint32_t)fold(s[f][2], m); r.w = (uint32_t)fold(s[f][3], m);
+        *reinterpret_cast<U4*>(a.out + ((size_t)f * a.G + g) * ct_words + pos) = r;
+      }
     }
   }
 };

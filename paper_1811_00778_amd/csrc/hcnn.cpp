@@ -221,6 +221,7 @@ template <> struct KernelClass<DigitKernel> { static constexpr int id = HCNN_PRO
 template <> struct KernelClass<RelinMacKernel> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
 template <> struct KernelClass<RelinAddKernel> { static constexpr int id = HCNN_PROF_RELIN_ADD; };
 template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
+template <int F> struct KernelClass<MacKernelDirect<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 
 int take_event(hcnn_ctx* c, hcnn_event_t* ev) {
   if (!c->free_events.empty()) {
@@ -477,7 +478,9 @@ int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
 
 template <int FT>
 int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
-  return run<MacKernel<FT>>(c, grid, 0, a);
+  const size_t lds = MacKernel<FT>::lds_bytes(a.F, a.T);
+  if (lds <= 64 * 1024 && lds <= c->max_lds) return run<MacKernel<FT>>(c, grid, lds, a);
+  return run<MacKernelDirect<FT>>(c, grid, 0, a);
 }
 
 int mac_dispatch(hcnn_ctx* c, size_t grid, const MacArgs& a) {

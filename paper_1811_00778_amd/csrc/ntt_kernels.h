@@ -44,8 +44,16 @@ HCNN_HD size_t ntt_row(uint32_t r, uint32_t cycle, uint32_t group_rows, uint32_t
   return (size_t)(r / cycle) * group_rows + row0 + r % cycle;
 }
 
-// LDS index swizzle: spreads power-of-two strides over the 32 banks.
-HCNN_HD uint32_t lds_swz(uint32_t i) { return i ^ ((i >> 5) & 31u); }
+// LDS index swizzle: spreads power-of-two strides over the 32 banks.  It is linear over XOR,
+// swz(a ^ b) = swz(a) ^ swz(b), and leaves bits >= 5 alone; the element e of a network sits at
+// base | (e << LOG_TLAST) with those bits of base clear, so its LDS word is
+// (swz(base) ^ low) + high with compile-time low = swz(field) & 1023 and high = field & ~1023.
+HCNN_HD constexpr uint32_t lds_swz(uint32_t i) { return i ^ ((i >> 5) & 31u); }
+template <int LOG_TLAST>
+HCNN_HD constexpr uint32_t lds_elem(uint32_t sbase, int e) {
+  const uint32_t field = (uint32_t)e << LOG_TLAST;
+  return (sbase ^ (lds_swz(field) & 1023u)) + (field & ~1023u);
+}
 
 template <int LOGN, int LOGR>
 struct NttGeom {
@@ -86,12 +94,11 @@ struct NttFwd {
       const uint32_t nu = (uint32_t)tid + (uint32_t)kThreads * c;   // network id
       const uint32_t o = nu & (TLAST - 1), i = nu >> LOG_TLAST;
       const uint32_t base = i * (uint32_t)(NET * TLAST) + o;        // element e at base + e*TLAST
+      const uint32_t sbase = lds_swz(base);
       uint32_t v[NET];
 #pragma unroll
-      for (int e = 0; e < NET; ++e) {
-        const uint32_t idx = base + (uint32_t)e * TLAST;
-        v[e] = kFirst ? gin[idx] : lds[lds_swz(idx)];
-      }
+      for (int e = 0; e < NET; ++e)
+        v[e] = kFirst ? gin[base + (uint32_t)e * TLAST] : lds[lds_elem<LOG_TLAST>(sbase, e)];
       const uint32_t root = (1u << S0) + i;
 #pragma unroll
       for (int l = 0; l < NS; ++l) {
@@ -102,10 +109,10 @@ struct NttFwd {
 #pragma unroll
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
-            const uint32_t X = csub(v[ia], two_p);                      // [0, 2p)
-            const uint32_t T = shoup_lazy(v[ib], w.w, w.ws, p);        // [0, 2p)
-            v[ia] = X + T;                                             // [0, 4p)
-            v[ib] = X + two_p - T;                                     // (0, 4p)
+            const uint32_t X = csub(v[ia], two_p);                          // [0, 2p)
+            const uint32_t negT = mulhi32(v[ib], w.ws) * p - v[ib] * w.w;   // -(y*w mod p) - {0,p}  (mod 2^32)
+            v[ia] = X - negT;                                              // X + T        in [0, 4p)
+            v[ib] = X + two_p + negT;                                      // X - T + 2p   in (0, 4p)
           }
         }
       }
@@ -124,9 +131,8 @@ struct NttFwd {
       } else {
 #pragma unroll
         for (int e = 0; e < NET; ++e) {
-          const uint32_t idx = base + (uint32_t)e * TLAST;
-          if (kLast) gout[idx] = csub(csub(v[e], two_p), p);
-          else       lds[lds_swz(idx)] = v[e];
+          if (kLast) gout[base + (uint32_t)e * TLAST] = csub(csub(v[e], two_p), p);
+          else       lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
         }
       }
     }
@@ -161,6 +167,7 @@ struct NttInv {
       const uint32_t nu = (uint32_t)tid + (uint32_t)kThreads * c;
       const uint32_t o = nu & (TLAST - 1), i = nu >> LOG_TLAST;
       const uint32_t base = i * (uint32_t)(NET * TLAST) + o;
+      const uint32_t sbase = lds_swz(base);
       uint32_t v[NET];
       if constexpr (kFirst && NET >= 4) {
         // TLAST == 1: NET consecutive coefficients -> 16-byte loads
@@ -172,10 +179,8 @@ struct NttInv {
         }
       } else {
 #pragma unroll
-        for (int e = 0; e < NET; ++e) {
-          const uint32_t idx = base + (uint32_t)e * TLAST;
-          v[e] = kFirst ? gin[idx] : lds[lds_swz(idx)];     // [0, 2p)
-        }
+        for (int e = 0; e < NET; ++e)
+          v[e] = kFirst ? gin[base + (uint32_t)e * TLAST] : lds[lds_elem<LOG_TLAST>(sbase, e)];   // [0, 2p)
       }
       const uint32_t root = (1u << S0) + i;
 #pragma unroll
@@ -198,9 +203,8 @@ struct NttInv {
       }
 #pragma unroll
       for (int e = 0; e < NET; ++e) {
-        const uint32_t idx = base + (uint32_t)e * TLAST;
-        if (kLast) gout[idx] = csub(v[e], p);
-        else       lds[lds_swz(idx)] = v[e];
+        if (kLast) gout[base + (uint32_t)e * TLAST] = csub(v[e], p);
+        else       lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
       }
     }
   }

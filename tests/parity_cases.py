@@ -128,6 +128,9 @@ def check_scalar_mac(backend, n, k, seed_id=1):
     w[0, 0, :] = big
     w[0, 1, :] = -big
     run(idx[:2].copy(), w, big)
+    # a gather row too long for the LDS-staged kernel takes the direct variant ((1+F)*T*4 > 64 KiB)
+    long_idx = s.rng.integers(0, n_in, size=(1, 5000)).astype(np.uint32)
+    run(long_idx, gen.int_weights(s.rng, (1, 3, 5000), 100), 100)
     # all-zero weights and bound 0
     run(idx[:1].copy(), np.zeros((1, 2, 7), dtype=np.int32), 0)
     assert s.ctx.bad_inputs() == 0
