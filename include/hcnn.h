@@ -182,18 +182,18 @@ int hcnn_set_option(hcnn_ctx* ctx, int which, uint64_t value);
 /* Per-kernel timing collected while HCNN_OPT_PROFILE is on.  One class per kernel of the hot
  * path (the classes follow the steps of HMult in Sec. 2.1 and the layer sum of Sec. 4.3).
  * `blocks` is the number of workgroups launched: one (polynomial, limb) row of n residues per
- * workgroup for the two NTT classes, 256 coefficient positions (1024 for TENSOR, DIGIT,
- * RELIN_MAC, RELIN_ADD and SCALAR_MAC) per workgroup for the others.
+ * workgroup for the two NTT classes, 256 coefficient positions (1024 for RELIN_MAC and
+ * SCALAR_MAC) per workgroup for the others.
  * hcnn_profile_read synchronises the stream; hcnn_reset_stats clears the accumulators. */
 enum {
   HCNN_PROF_NTT_FWD = 0,
   HCNN_PROF_NTT_INV = 1,
   HCNN_PROF_BASE_EXT = 2,    /* centred lift q -> q u p                              */
-  HCNN_PROF_TENSOR = 3,      /* (c0^2, 2 c0 c1, c1^2) slot-wise                      */
+  HCNN_PROF_TENSOR = 3,      /* (c0^2, 2 c0 c1, c1^2) slot-wise: fused into NTT_INV, stays 0 */
   HCNN_PROF_SCALE = 4,       /* round(t/q .) and return to basis q                   */
-  HCNN_PROF_DIGIT = 5,       /* RNS digits of c2 reduced modulo every prime          */
+  HCNN_PROF_DIGIT = 5,       /* RNS digits of c2 mod every prime: fused into NTT_FWD, stays 0 */
   HCNN_PROF_RELIN_MAC = 6,   /* inner product with the evaluation key                */
-  HCNN_PROF_RELIN_ADD = 7,
+  HCNN_PROF_RELIN_ADD = 7,   /* final addition: fused into NTT_INV, stays 0           */
   HCNN_PROF_SCALAR_MAC = 8,
   HCNN_PROF_OTHER = 9,
   HCNN_PROF_COUNT = 10

@@ -54,17 +54,17 @@ HCNN_HD uint32_t frac31(uint32_t z, const Mod& m) { return mulhi32(z << 2, m.mu)
 // by its mixed-radix digits.  Returns 1 when X > (M-1)/2.
 HCNN_HD uint32_t garner_gt_half(const BConvDev& bc, uint32_t* col, int stride) {
   for (uint32_t i = 1; i < bc.ks; ++i) {
-    const Mod m = bc.src_mod[i];
+    const Mod m = ldc(bc.src_mod, i);
     uint32_t t = col[i * stride];
     for (uint32_t l = 0; l < i; ++l) {
       const uint32_t al = reduce32(col[l * stride], m);
       t = sub_mod(t, al, m.p);
-      t = mul_mod(t, bc.ginv[i * bc.ks + l], m);
+      t = mul_mod(t, ldc(bc.ginv, i * bc.ks + l), m);
     }
     col[i * stride] = t;
   }
   for (int i = (int)bc.ks - 1; i >= 0; --i) {
-    const uint32_t a = col[i * stride], h = bc.half[i];
+    const uint32_t a = col[i * stride], h = ldc(bc.half, i);
     if (a > h) return 1;
     if (a < h) return 0;
   }
@@ -96,13 +96,13 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
                                uint32_t band, unsigned long long* fallback_counter) {
   uint64_t S = 0;
   for (uint32_t i = 0; i < bc.ks; ++i) {
-    const Mod m = bc.src_mod[i];
-    const uint32_t z = shoup_mul(in(i), bc.zmul[i], m.p);
+    const Mod m = ldc(bc.src_mod, i);
+    const uint32_t z = shoup_mul(in(i), ldc(bc.zmul, i), m.p);
     zcol[i * stride] = z;
     S += frac31(z, m);
   }
   auto exact = [&]() {
-    for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), bc.xmul[i], bc.src_mod[i].p);
+    for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), ldc(bc.xmul, i), ldc(bc.src_mod, i).p);
     return garner_gt_half(bc, gcol, stride);
   };
   return bconv_round(S, band, exact, fallback_counter);
@@ -111,10 +111,10 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
 // Residue of the converted integer modulo destination j; `extra` (< 2^60) is added before reducing.
 HCNN_HD uint32_t bconv_output(const BConvDev& bc, const uint32_t* zcol, int stride, uint32_t v, uint32_t j,
                               uint64_t extra = 0) {
-  const Mod dm = bc.dst_mod[j];
-  uint64_t acc = extra + (uint64_t)v * bc.Vp[j];
+  const Mod dm = ldc(bc.dst_mod, j);
+  uint64_t acc = extra + (uint64_t)v * ldc(bc.Vp, j);
   for (uint32_t i = 0; i < bc.ks; ++i) {
-    acc += (uint64_t)zcol[i * stride] * bc.Bp[i * bc.kd + j];
+    acc += (uint64_t)zcol[i * stride] * ldc(bc.Bp, i * bc.kd + j);
     if ((i & 7u) == 7u) acc = reduce64(acc, dm);
   }
   return reduce64(acc, dm);
@@ -175,14 +175,14 @@ struct ExtKernelT {
     for (int i = 0; i < K; ++i) x[i] = src[(size_t)i * n];
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      const Mod m = a.bc.src_mod[i];
-      z[i] = shoup_mul(x[i], a.bc.zmul[i], m.p);
+      const Mod m = ldc(a.bc.src_mod, i);
+      z[i] = shoup_mul(x[i], ldc(a.bc.zmul, i), m.p);
       S += frac31(z[i], m);
     }
     auto exact = [&]() {
       uint32_t* col = lds + tid;
 #pragma unroll
-      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(x[i], a.bc.xmul[i], a.bc.src_mod[i].p);
+      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(x[i], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i).p);
       return garner_gt_half(a.bc, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact, a.fallback_counter);
@@ -190,50 +190,15 @@ struct ExtKernelT {
     for (int i = 0; i < K; ++i) dst[(size_t)i * n] = x[i];
 #pragma unroll
     for (int j = 0; j < KP; ++j) {
-      const Mod dm = a.bc.dst_mod[j];
-      uint64_t acc = (uint64_t)v * a.bc.Vp[j];
+      const Mod dm = ldc(a.bc.dst_mod, j);
+      uint64_t acc = (uint64_t)v * ldc(a.bc.Vp, j);
 #pragma unroll
       for (int i = 0; i < K; ++i) {
-        acc += (uint64_t)z[i] * a.bc.Bp[i * KP + j];
+        acc += (uint64_t)z[i] * ldc(a.bc.Bp, i * KP + j);
         if ((i & 7) == 7 && i + 1 < K) acc = reduce64(acc, dm);
       }
       dst[(size_t)(K + j) * n] = reduce64(acc, dm);
     }
-  }
-};
-
-// ---------------------------------------------------------------- tensor (squaring), NTT domain
-// ext [n_ct][2][L][n] -> d [n_ct][3][L][n]: d0 = c0*c0, d1 = 2*c0*c1, d2 = c1*c1 (HMult step 1 with c = c').
-struct TensorArgs {
-  const uint32_t* ext;
-  uint32_t* d;
-  const Mod* mods;   // [L]
-  uint32_t L, n;
-};
-struct TensorSqKernel {
-  static constexpr int kThreads = kEwThreads;
-  static constexpr int kPhases = 1;
-  struct Regs {};
-  template <int PH>
-  HCNN_HD static void phase(const TensorArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
-    const uint32_t per_row = a.n / (kThreads * kEwVec);
-    const size_t row = bid / per_row;                       // (ct, limb)
-    const uint32_t c = ((bid % per_row) * kThreads + tid) * kEwVec;
-    const size_t ct = row / a.L;
-    const uint32_t l = (uint32_t)(row % a.L);
-    const Mod m = a.mods[l];
-    const size_t rn = (size_t)a.n;
-    const U4 x = *reinterpret_cast<const U4*>(a.ext + ((ct * 2 + 0) * a.L + l) * rn + c);
-    const U4 y = *reinterpret_cast<const U4*>(a.ext + ((ct * 2 + 1) * a.L + l) * rn + c);
-    U4 d0, d1, d2;
-    auto twice = [&](uint32_t v) { return csub(2 * v, m.p); };
-    d0.x = mul_mod(x.x, x.x, m); d1.x = twice(mul_mod(x.x, y.x, m)); d2.x = mul_mod(y.x, y.x, m);
-    d0.y = mul_mod(x.y, x.y, m); d1.y = twice(mul_mod(x.y, y.y, m)); d2.y = mul_mod(y.y, y.y, m);
-    d0.z = mul_mod(x.z, x.z, m); d1.z = twice(mul_mod(x.z, y.z, m)); d2.z = mul_mod(y.z, y.z, m);
-    d0.w = mul_mod(x.w, x.w, m); d1.w = twice(mul_mod(x.w, y.w, m)); d2.w = mul_mod(y.w, y.w, m);
-    *reinterpret_cast<U4*>(a.d + ((ct * 3 + 0) * a.L + l) * rn + c) = d0;
-    *reinterpret_cast<U4*>(a.d + ((ct * 3 + 1) * a.L + l) * rn + c) = d1;
-    *reinterpret_cast<U4*>(a.d + ((ct * 3 + 2) * a.L + l) * rn + c) = d2;
   }
 };
 
@@ -275,7 +240,7 @@ struct ScaleKernel {
     auto in_q = [&](uint32_t i) { return src[(size_t)i * n]; };
     const uint32_t v = bconv_prepare(a.to_p, in_q, zcol, gcol, kThreads, a.band, a.fallback_counter);
     for (uint32_t j = 0; j < kp; ++j) {
-      const uint64_t extra = (uint64_t)src[(size_t)(k + j) * n] * a.tq_inv[j];
+      const uint64_t extra = (uint64_t)src[(size_t)(k + j) * n] * ldc(a.tq_inv, j);
       ycol[j * kThreads] = bconv_output(a.to_p, zcol, kThreads, v, j, extra);
     }
     auto in_p = [&](uint32_t j) { return ycol[j * kThreads]; };
@@ -311,23 +276,23 @@ struct ScaleKernelT {
     uint64_t S = 0;
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      const Mod m = a.to_p.src_mod[i];
-      z[i] = shoup_mul(dq[i], a.to_p.zmul[i], m.p);
+      const Mod m = ldc(a.to_p.src_mod, i);
+      z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m.p);
       S += frac31(z[i], m);
     }
     auto exact_q = [&]() {
 #pragma unroll
-      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(dq[i], a.to_p.xmul[i], a.to_p.src_mod[i].p);
+      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(dq[i], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i).p);
       return garner_gt_half(a.to_p, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact_q, a.fallback_counter);
 #pragma unroll
     for (int j = 0; j < KP; ++j) {
-      const Mod dm = a.to_p.dst_mod[j];
-      uint64_t acc = (uint64_t)dp[j] * a.tq_inv[j] + (uint64_t)v * a.to_p.Vp[j];
+      const Mod dm = ldc(a.to_p.dst_mod, j);
+      uint64_t acc = (uint64_t)dp[j] * ldc(a.tq_inv, j) + (uint64_t)v * ldc(a.to_p.Vp, j);
 #pragma unroll
       for (int i = 0; i < K; ++i) {
-        acc += (uint64_t)z[i] * a.to_p.Bp[i * KP + j];
+        acc += (uint64_t)z[i] * ldc(a.to_p.Bp, i * KP + j);
         if ((i & 7) == 7 && i + 1 < K) acc = reduce64(acc, dm);
       }
       y[j] = reduce64(acc, dm);
@@ -336,8 +301,8 @@ struct ScaleKernelT {
     uint64_t S2 = 0;
 #pragma unroll
     for (int j = 0; j < KP; ++j) {
-      const Mod m = a.to_q.src_mod[j];
-      z[j < (K > KP ? K : KP) ? j : 0] = shoup_mul(y[j], a.to_q.zmul[j], m.p);
+      const Mod m = ldc(a.to_q.src_mod, j);
+      z[j < (K > KP ? K : KP) ? j : 0] = shoup_mul(y[j], ldc(a.to_q.zmul, j), m.p);
       S2 += frac31(z[j], m);
     }
     auto exact_p = [&]() {
@@ -348,11 +313,11 @@ struct ScaleKernelT {
     const uint32_t v2 = bconv_round(S2, a.band, exact_p, a.fallback_counter);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      const Mod dm = a.to_q.dst_mod[i];
-      uint64_t acc = (uint64_t)v2 * a.to_q.Vp[i];
+      const Mod dm = ldc(a.to_q.dst_mod, i);
+      uint64_t acc = (uint64_t)v2 * ldc(a.to_q.Vp, i);
 #pragma unroll
       for (int j = 0; j < KP; ++j) {
-        acc += (uint64_t)z[j] * a.to_q.Bp[j * K + i];
+        acc += (uint64_t)z[j] * ldc(a.to_q.Bp, j * K + i);
         if ((j & 7) == 7 && j + 1 < KP) acc = reduce64(acc, dm);
       }
       dst[(size_t)i * n] = reduce64(acc, dm);
@@ -360,36 +325,8 @@ struct ScaleKernelT {
   }
 };
 
-// ---------------------------------------------------------------- relinearisation pieces
-// y2 rows [n_ct][3][k][n] component 2 -> digits [n_ct][k(i)][k(j)][n]: digit i reduced mod q_j.
-struct DigitArgs {
-  const uint32_t* y;     // [n_ct][3][k][n]
-  uint32_t* dig;         // [n_ct][k][k][n]
-  const Mod* mods;       // [k] (q)
-  uint32_t k, n;
-};
-struct DigitKernel {
-  static constexpr int kThreads = kEwThreads;
-  static constexpr int kPhases = 1;
-  struct Regs {};
-  template <int PH>
-  HCNN_HD static void phase(const DigitArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
-    const uint32_t per_row = a.n / (kThreads * kEwVec);
-    const size_t row = bid / per_row;                       // (ct, i)
-    const uint32_t c = ((bid % per_row) * kThreads + tid) * kEwVec;
-    const size_t ct = row / a.k;
-    const uint32_t i = (uint32_t)(row % a.k);
-    const size_t rn = a.n;
-    const U4 x = *reinterpret_cast<const U4*>(a.y + ((ct * 3 + 2) * a.k + i) * rn + c);
-    for (uint32_t j = 0; j < a.k; ++j) {
-      const Mod m = a.mods[j];
-      U4 r;
-      r.x = reduce32(x.x, m); r.y = reduce32(x.y, m); r.z = reduce32(x.z, m); r.w = reduce32(x.w, m);
-      *reinterpret_cast<U4*>(a.dig + ((ct * a.k + i) * a.k + j) * rn + c) = r;
-    }
-  }
-};
-
+// ---------------------------------------------------------------- relinearisation inner product
+// (the digit reduction and the final addition are fused into the transforms, see ntt_kernels.h)
 // acc[ct][b][j] = sum_i evk_hat[i][b][j] * dig_hat[ct][i][j]   (all NTT domain)
 struct RelinMacArgs {
   const uint32_t* dig;   // [n_ct][k][k][n]
@@ -409,7 +346,7 @@ struct RelinMacKernel {
     const uint32_t c = ((bid % per_row) * kThreads + tid) * kEwVec;
     const size_t ct = row / a.k;
     const uint32_t j = (uint32_t)(row % a.k);
-    const Mod m = a.mods[j];
+    const Mod m = ldc(a.mods, j);
     const size_t rn = a.n;
     uint64_t s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
     for (uint32_t i = 0; i < a.k; ++i) {
@@ -427,36 +364,6 @@ struct RelinMacKernel {
     r1.x = reduce64(s1[0], m); r1.y = reduce64(s1[1], m); r1.z = reduce64(s1[2], m); r1.w = reduce64(s1[3], m);
     *reinterpret_cast<U4*>(a.acc + ((ct * 2 + 0) * a.k + j) * rn + c) = r0;
     *reinterpret_cast<U4*>(a.acc + ((ct * 2 + 1) * a.k + j) * rn + c) = r1;
-  }
-};
-
-// out[ct][b][j] = y[ct][b][j] + acc[ct][b][j]  (coefficient domain)
-struct RelinAddArgs {
-  const uint32_t* y;     // [n_ct][3][k][n]
-  const uint32_t* acc;   // [n_ct][2][k][n]
-  uint32_t* out;         // [n_ct][2][k][n]
-  const Mod* mods;
-  uint32_t k, n;
-};
-struct RelinAddKernel {
-  static constexpr int kThreads = kEwThreads;
-  static constexpr int kPhases = 1;
-  struct Regs {};
-  template <int PH>
-  HCNN_HD static void phase(const RelinAddArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
-    const uint32_t per_row = a.n / (kThreads * kEwVec);
-    const size_t row = bid / per_row;                       // (ct, b, j)
-    const uint32_t c = ((bid % per_row) * kThreads + tid) * kEwVec;
-    const uint32_t j = (uint32_t)(row % a.k);
-    const size_t cb = row / a.k;
-    const size_t ct = cb / 2, b = cb % 2;
-    const uint32_t p = a.mods[j].p;
-    const size_t rn = a.n;
-    const U4 u = *reinterpret_cast<const U4*>(a.y + ((ct * 3 + b) * a.k + j) * rn + c);
-    const U4 w = *reinterpret_cast<const U4*>(a.acc + row * rn + c);
-    U4 r;
-    r.x = add_mod(u.x, w.x, p); r.y = add_mod(u.y, w.y, p); r.z = add_mod(u.z, w.z, p); r.w = add_mod(u.w, w.w, p);
-    *reinterpret_cast<U4*>(a.out + row * rn + c) = r;
   }
 };
 
@@ -496,7 +403,7 @@ struct MacKernelDirect {
     const uint32_t pos = (tile * kThreads + tid) * kEwVec;            // word offset inside a ciphertext
     const uint32_t row = tile / (a.n / (kThreads * kEwVec));          // (poly, limb) row; uniform in the block
     const uint32_t limb = row % a.k;
-    const Mod m = a.mods[limb];
+    const Mod m = ldc(a.mods, limb);
     const uint32_t* idx = a.idx + (size_t)g * a.T;
     const int32_t* w = a.w + (size_t)g * a.F * a.T;
     int64_t s[FT][4];
@@ -583,7 +490,7 @@ struct MacKernel {
     } else {
       const uint32_t pos = (tile * kThreads + tid) * kEwVec;          // word offset inside a ciphertext
       const uint32_t row = tile / (a.n / (kThreads * kEwVec));        // (poly, limb) row; uniform in the block
-      const Mod m = a.mods[row % a.k];
+      const Mod m = ldc(a.mods, row % a.k);
       const uint32_t* in = a.in + pos;
       int64_t s[FT][4];
 #pragma unroll
@@ -636,7 +543,7 @@ struct SmallToRnsKernel {
     const size_t poly = bid / per_poly;
     const uint32_t c = (bid % per_poly) * kThreads + tid;
     const int32_t v = a.small[poly * a.n + c];
-    for (uint32_t l = 0; l < a.k; ++l) a.out[(poly * a.k + l) * a.n + c] = small_to_res(v, a.mods[l]);
+    for (uint32_t l = 0; l < a.k; ++l) a.out[(poly * a.k + l) * a.n + c] = small_to_res(v, ldc(a.mods, l));
   }
 };
 
@@ -660,7 +567,7 @@ struct PointMulKernel {
     const uint32_t per_row = a.n / kThreads;
     const size_t row = bid / per_row;
     const uint32_t c = (bid % per_row) * kThreads + tid;
-    const Mod m = a.mods[row % a.k];
+    const Mod m = ldc(a.mods, row % a.k);
     const uint32_t x = a.a[(row % a.a_cycle) * a.n + c];
     const uint32_t y = a.b[(row % a.b_cycle) * a.n + c];
     uint32_t r = mul_mod(x, y, m);
@@ -692,10 +599,10 @@ struct AddSmallKernel {
     const uint32_t c = (bid % per_row) * kThreads + tid;
     const size_t poly = row / a.k;
     const uint32_t l = (uint32_t)(row % a.k);
-    const Mod m = a.mods[l];
+    const Mod m = ldc(a.mods, l);
     const uint32_t sv = small_to_res(a.small[poly * a.n + c], m);
     uint32_t r = a.subtract_small ? sub_mod(a.x[row * a.n + c], sv, m.p) : add_mod(a.x[row * a.n + c], sv, m.p);
-    if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), a.scale[l], m.p), m.p);
+    if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
     a.out[(poly * a.out_poly_rows + a.out_row0 + l) * a.n + c] = r;
   }
 };
@@ -717,7 +624,7 @@ struct AddDiagKernel {
     const uint32_t i = bid / per_row;
     const uint32_t c = (bid % per_row) * kThreads + tid;
     uint32_t* dst = a.evk + (((size_t)i * 2 + 0) * a.k + i) * a.n + c;
-    *dst = add_mod(*dst, a.s2[(size_t)i * a.n + c], a.mods[i].p);
+    *dst = add_mod(*dst, a.s2[(size_t)i * a.n + c], ldc(a.mods, i).p);
   }
 };
 
@@ -741,7 +648,7 @@ struct AddRowsKernel {
     const uint32_t c = (bid % per_row) * kThreads + tid;
     const size_t poly = row / a.k;
     const uint32_t l = (uint32_t)(row % a.k);
-    const uint32_t p = a.mods[l].p;
+    const uint32_t p = ldc(a.mods, l).p;
     a.c[row * a.n + c] = add_mod(a.a[(poly * a.a_poly_rows + a.a_row0 + l) * a.n + c], a.b[row * a.n + c], p);
   }
 };
@@ -774,8 +681,8 @@ struct DecRoundKernel {
     auto in = [&](uint32_t i) { return src[(size_t)i * n]; };
     const uint32_t v = bconv_prepare(a.bc, in, zcol, gcol, kThreads, a.band, a.fallback_counter);
     // the destination modulus t is small: plain 64-bit remainder (test helper, not tuned)
-    uint64_t acc = ((uint64_t)v * a.bc.Vp[0]) % a.t;
-    for (uint32_t i = 0; i < ks; ++i) acc = (acc + (uint64_t)zcol[i * kThreads] * a.bc.Bp[i]) % a.t;
+    uint64_t acc = ((uint64_t)v * ldc(a.bc.Vp, 0)) % a.t;
+    for (uint32_t i = 0; i < ks; ++i) acc = (acc + (uint64_t)zcol[i * kThreads] * ldc(a.bc.Bp, i)) % a.t;
     a.m_out[poly * n + c] = (uint32_t)((acc * a.neg_qinv_t) % a.t);
   }
 };

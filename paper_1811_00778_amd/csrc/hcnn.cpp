@@ -210,16 +210,13 @@ int upload(hcnn_ctx* c, const std::vector<T>& h, T** d) {
 }
 
 template <class K> struct KernelClass { static constexpr int id = HCNN_PROF_OTHER; };
-template <int A, int B> struct KernelClass<NttFwd<A, B>> { static constexpr int id = HCNN_PROF_NTT_FWD; };
-template <int A, int B> struct KernelClass<NttInv<A, B>> { static constexpr int id = HCNN_PROF_NTT_INV; };
+template <int A, int B, int C> struct KernelClass<NttFwd<A, B, C>> { static constexpr int id = HCNN_PROF_NTT_FWD; };
+template <int A, int B, int C> struct KernelClass<NttInv<A, B, C>> { static constexpr int id = HCNN_PROF_NTT_INV; };
 template <> struct KernelClass<ExtKernel> { static constexpr int id = HCNN_PROF_BASE_EXT; };
 template <int A, int B> struct KernelClass<ExtKernelT<A, B>> { static constexpr int id = HCNN_PROF_BASE_EXT; };
 template <int A, int B> struct KernelClass<ScaleKernelT<A, B>> { static constexpr int id = HCNN_PROF_SCALE; };
-template <> struct KernelClass<TensorSqKernel> { static constexpr int id = HCNN_PROF_TENSOR; };
 template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
-template <> struct KernelClass<DigitKernel> { static constexpr int id = HCNN_PROF_DIGIT; };
 template <> struct KernelClass<RelinMacKernel> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
-template <> struct KernelClass<RelinAddKernel> { static constexpr int id = HCNN_PROF_RELIN_ADD; };
 template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 template <int F> struct KernelClass<MacKernelDirect<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 
@@ -421,39 +418,45 @@ struct NttRows {
   size_t rows;
   uint32_t cycle, limb_base;
   uint32_t in_group_rows, in_row0, out_group_rows, out_row0;
+  const uint32_t* aux = nullptr;
 };
 
 template <int LOGN, int LOGR>
-int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse) {
+int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse, int io) {
   NttArgs a;
-  a.in = r.in; a.out = r.out;
+  a.in = r.in; a.out = r.out; a.aux = r.aux;
   a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
   a.limbs = c->d_limbs;
   a.limb_cycle = r.cycle; a.limb_base = r.limb_base;
   a.in_group_rows = r.in_group_rows; a.in_row0 = r.in_row0;
   a.out_group_rows = r.out_group_rows; a.out_row0 = r.out_row0;
   const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;
-  if (inverse) return run<NttInv<LOGN, LOGR>>(c, r.rows, lds, a);
+  if (inverse) {
+    if (io == kNttLoadTensor) return run<NttInv<LOGN, LOGR, kNttLoadTensor>>(c, r.rows, lds, a);
+    if (io == kNttStoreAdd) return run<NttInv<LOGN, LOGR, kNttStoreAdd>>(c, r.rows, lds, a);
+    return run<NttInv<LOGN, LOGR>>(c, r.rows, lds, a);
+  }
+  if (io == kNttLoadDigit) return run<NttFwd<LOGN, LOGR, kNttLoadDigit>>(c, r.rows, lds, a);
   return run<NttFwd<LOGN, LOGR>>(c, r.rows, lds, a);
 }
 
-int ntt_rows(hcnn_ctx* c, const NttRows& r, bool inverse) {
+int ntt_rows(hcnn_ctx* c, const NttRows& r, bool inverse, int io = kNttPlain) {
   switch (c->logn) {
-    case 10: return ntt_launch<10, 4>(c, r, inverse);
-    case 11: return ntt_launch<11, 4>(c, r, inverse);
-    case 12: return ntt_launch<12, 4>(c, r, inverse);
-    case 13: return ntt_launch<13, 5>(c, r, inverse);
-    case 14: return ntt_launch<14, 5>(c, r, inverse);
-    case 15: return ntt_launch<15, 5>(c, r, inverse);
+    case 10: return ntt_launch<10, 4>(c, r, inverse, io);
+    case 11: return ntt_launch<11, 4>(c, r, inverse, io);
+    case 12: return ntt_launch<12, 4>(c, r, inverse, io);
+    case 13: return ntt_launch<13, 5>(c, r, inverse, io);
+    case 14: return ntt_launch<14, 5>(c, r, inverse, io);
+    case 15: return ntt_launch<15, 5>(c, r, inverse, io);
   }
   return HCNN_ERR_N;
 }
 
 // dense rows [rows][n], limb = base + r % cycle
 int ntt_dense(hcnn_ctx* c, const uint32_t* in, uint32_t* out, size_t rows, uint32_t cycle, bool inverse,
-              uint32_t limb_base = 0) {
-  NttRows r{in, out, rows, cycle, limb_base, cycle, 0, cycle, 0};
-  return ntt_rows(c, r, inverse);
+              int io = kNttPlain, const uint32_t* aux = nullptr) {
+  NttRows r{in, out, rows, cycle, 0, cycle, 0, cycle, 0, aux};
+  return ntt_rows(c, r, inverse, io);
 }
 
 // Base-conversion kernels: register-resident variants for the basis sizes of the standard
@@ -696,31 +699,22 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
     // 2. forward NTT over all k + k' limbs
     if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false))) return e;
-    // 3. tensor: (c0^2, 2 c0 c1, c1^2)
-    TensorArgs ta;
-    ta.ext = ext; ta.d = d; ta.mods = c->d_mods; ta.L = L; ta.n = n;
-    if ((e = run<TensorSqKernel>(c, cc * L * bpr, 0, ta))) return e;
-    // 4. back to coefficients: the integer tensor, known mod q*p
-    if ((e = ntt_dense(c, d, d, cc * 3 * L, L, true))) return e;
+    // 3+4. tensor (c0^2, 2 c0 c1, c1^2) formed while loading, then back to coefficients: the integer
+    //      tensor, known mod q*p
+    if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensor))) return e;
     // 5. y = round(t/q * d) mod q
     ScaleArgs sa;
     sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
     sa.band = c->band; sa.fallback_counter = c->d_counters;
     if ((e = scale_dispatch(c, cc * 3 * bpp, sa))) return e;
-    // 6. RNS digits of y2, each reduced modulo every q_j, then transformed
-    DigitArgs da;
-    da.y = y; da.dig = dig; da.mods = c->d_mods; da.k = k; da.n = n;
-    if ((e = run<DigitKernel>(c, cc * k * bpr, 0, da))) return e;
-    if ((e = ntt_dense(c, dig, dig, cc * k * k, k, false))) return e;
+    // 6. RNS digits of y2, each reduced modulo every q_j while loading, transformed
+    if ((e = ntt_dense(c, y, dig, cc * k * k, k, false, kNttLoadDigit))) return e;
     // 7. inner product with the evaluation key
     RelinMacArgs ra;
     ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
     if ((e = run<RelinMacKernel>(c, cc * k * bpr, 0, ra))) return e;
-    if ((e = ntt_dense(c, acc, acc, cc * 2 * k, k, true))) return e;
-    // 8. c'_b = y_b + sum_i evk[i][b] * digit_i
-    RelinAddArgs aa;
-    aa.y = y; aa.acc = acc; aa.out = out + c0 * ct_words; aa.mods = c->d_mods; aa.k = k; aa.n = n;
-    if ((e = run<RelinAddKernel>(c, cc * 2 * k * bpr, 0, aa))) return e;
+    // 8. c'_b = y_b + sum_i evk[i][b] * digit_i : inverse transform with the addition on the way out
+    if ((e = ntt_dense(c, acc, out + c0 * ct_words, cc * 2 * k, k, true, kNttStoreAdd, y))) return e;
   }
   return HCNN_OK;
 }

@@ -29,9 +29,20 @@ struct NttLimb {
 // Row r (= workgroup index) belongs to group r / limb_cycle and limb limb_base + r % limb_cycle.
 // Its data sits at row (group * group_rows + row0 + r % limb_cycle) of the in / out arrays, so a
 // launch can pick one polynomial out of every ciphertext of a batch.
+// Fused input / output stages (template parameter IO of the kernels):
+//   kNttPlain       rows are read and written as they are
+//   kNttLoadDigit   forward only: row (ct, i, j) reads digit i of y2, i.e. row (ct*3+2)*k + i of `in`
+//                   = y[n_ct][3][k][n], reduced modulo q_j (one conditional subtraction: every prime
+//                   lies in (2^29, 2^30)); output rows dense [ct][i][j]
+//   kNttLoadTensor  inverse only: row (ct, b, l) reads c0^ = in[(ct*2)*L + l], c1^ = in[(ct*2+1)*L + l]
+//                   and transforms c0^*c0^, 2*c0^*c1^ or c1^*c1^ for b = 0, 1, 2 (HMult step 1, c = c')
+//   kNttStoreAdd    inverse only: row (ct, b, j) adds aux row (ct*3+b)*k + j (aux = y) on the way out
+enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3 };
+
 struct NttArgs {
   const uint32_t* in;
   uint32_t* out;            // may equal `in`
+  const uint32_t* aux;      // kNttStoreAdd only
   const ShoupConst* tw;     // [L][n] node table (forward or inverse)
   const NttLimb* limbs;     // [L]
   uint32_t limb_cycle;
@@ -68,8 +79,9 @@ struct NttGeom {
 };
 
 // ------------------------------------------------------------------------- forward
-template <int LOGN, int LOGR>
+template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttFwd {
+  static_assert(IO == kNttPlain || IO == kNttLoadDigit, "forward NTT: plain or digit load");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
@@ -83,10 +95,16 @@ struct NttFwd {
     constexpr bool kFirst = PH == 0, kLast = PH == kPhases - 1;
 
     const uint32_t limb = a.limb_base + bid % a.limb_cycle;
-    const NttLimb& L = a.limbs[limb];
+    const NttLimb L = ldc(a.limbs, limb);
     const uint32_t p = L.m.p, two_p = 2 * L.m.p;
     const ShoupConst* tw = a.tw + (size_t)limb * N;
-    const uint32_t* gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+    const uint32_t* gin;
+    if constexpr (IO == kNttLoadDigit) {
+      const uint32_t kk = a.limb_cycle;
+      gin = a.in + ((size_t)(bid / (kk * kk)) * 3 * kk + 2 * kk + (bid / kk) % kk) * N;
+    } else {
+      gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+    }
     uint32_t* gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
 
 #pragma unroll
@@ -99,13 +117,17 @@ struct NttFwd {
 #pragma unroll
       for (int e = 0; e < NET; ++e)
         v[e] = kFirst ? gin[base + (uint32_t)e * TLAST] : lds[lds_elem<LOG_TLAST>(sbase, e)];
+      if constexpr (kFirst && IO == kNttLoadDigit) {
+#pragma unroll
+        for (int e = 0; e < NET; ++e) v[e] = csub(v[e], p);
+      }
       const uint32_t root = (1u << S0) + i;
 #pragma unroll
       for (int l = 0; l < NS; ++l) {
         const int half = NET >> (l + 1);
 #pragma unroll
         for (int h = 0; h < (1 << l); ++h) {
-          const ShoupConst w = tw[(root << l) + h];
+          const ShoupConst w = ldc(tw, (root << l) + h);
 #pragma unroll
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
@@ -140,8 +162,9 @@ struct NttFwd {
 };
 
 // ------------------------------------------------------------------------- inverse
-template <int LOGN, int LOGR>
+template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttInv {
+  static_assert(IO == kNttPlain || IO == kNttLoadTensor || IO == kNttStoreAdd, "inverse NTT io mode");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
@@ -156,11 +179,27 @@ struct NttInv {
     constexpr bool kFirst = PHI == 0, kLast = PHI == kPhases - 1;   // kLast <=> S0 == 0
 
     const uint32_t limb = a.limb_base + bid % a.limb_cycle;
-    const NttLimb& L = a.limbs[limb];
+    const NttLimb L = ldc(a.limbs, limb);
     const uint32_t p = L.m.p, two_p = 2 * L.m.p;
     const ShoupConst* tw = a.tw + (size_t)limb * N;
-    const uint32_t* gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+    const uint32_t* gin;
+    const uint32_t* gin2 = nullptr;       // kNttLoadTensor: the c1^ row
+    uint32_t comp = 0;                    // kNttLoadTensor: tensor component b
+    if constexpr (IO == kNttLoadTensor) {
+      const uint32_t LL = a.limb_cycle;
+      const uint32_t ct = bid / (3 * LL);
+      comp = (bid / LL) % 3;
+      gin2 = a.in + ((size_t)(ct * 2 + 1) * LL + bid % LL) * N;     // c1^
+      gin = comp == 2 ? gin2 : gin2 - (size_t)LL * N;                 // c0^ unless b = 2
+    } else {
+      gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+    }
     uint32_t* gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+    const uint32_t* gaux = nullptr;
+    if constexpr (IO == kNttStoreAdd) {
+      const uint32_t kk = a.limb_cycle, grp = bid / kk;
+      gaux = a.aux + ((size_t)(grp / 2) * 3 * kk + (size_t)(grp % 2) * kk + bid % kk) * N;
+    }
 
 #pragma unroll
     for (int c = 0; c < C; ++c) {
@@ -174,13 +213,32 @@ struct NttInv {
         const U4* g4 = reinterpret_cast<const U4*>(gin + base);
 #pragma unroll
         for (int e = 0; e < NET; e += 4) {
-          const U4 t = g4[e / 4];
+          U4 t = g4[e / 4];
+          if constexpr (IO == kNttLoadTensor) {
+            // gin was pointed at c0^ (b = 0, 1) or c1^ (b = 2); only b = 1 needs the second row
+            U4 y = t;
+            if (comp == 1) y = reinterpret_cast<const U4*>(gin2 + base)[e / 4];
+            t.x = mul_mod(t.x, y.x, L.m); t.y = mul_mod(t.y, y.y, L.m);
+            t.z = mul_mod(t.z, y.z, L.m); t.w = mul_mod(t.w, y.w, L.m);
+            if (comp == 1) { t.x = csub(2 * t.x, p); t.y = csub(2 * t.y, p); t.z = csub(2 * t.z, p); t.w = csub(2 * t.w, p); }
+          }
           v[e + 0] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
         }
       } else {
 #pragma unroll
-        for (int e = 0; e < NET; ++e)
-          v[e] = kFirst ? gin[base + (uint32_t)e * TLAST] : lds[lds_elem<LOG_TLAST>(sbase, e)];   // [0, 2p)
+        for (int e = 0; e < NET; ++e) {
+          if constexpr (kFirst) {
+            uint32_t t = gin[base + (uint32_t)e * TLAST];
+            if constexpr (IO == kNttLoadTensor) {
+              const uint32_t u = comp == 1 ? gin2[base + (uint32_t)e * TLAST] : t;
+              t = mul_mod(t, u, L.m);
+              if (comp == 1) t = csub(2 * t, p);
+            }
+            v[e] = t;
+          } else {
+            v[e] = lds[lds_elem<LOG_TLAST>(sbase, e)];   // [0, 2p)
+          }
+        }
       }
       const uint32_t root = (1u << S0) + i;
 #pragma unroll
@@ -189,7 +247,7 @@ struct NttInv {
         const bool top = kLast && l == 0;                 // node 1: fold in n^-1
 #pragma unroll
         for (int h = 0; h < (1 << l); ++h) {
-          const ShoupConst w = top ? L.w1ninv : tw[(root << l) + h];
+          const ShoupConst w = top ? L.w1ninv : ldc(tw, (root << l) + h);
 #pragma unroll
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
@@ -201,10 +259,19 @@ struct NttInv {
           }
         }
       }
+      if constexpr (kLast && IO == kNttStoreAdd) {
+        // all loads of the addend before the first store (the compiler must assume the buffers alias)
+        uint32_t addend[NET];
 #pragma unroll
-      for (int e = 0; e < NET; ++e) {
-        if (kLast) gout[base + (uint32_t)e * TLAST] = csub(v[e], p);
-        else       lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
+        for (int e = 0; e < NET; ++e) addend[e] = gaux[base + (uint32_t)e * TLAST];
+#pragma unroll
+        for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = add_mod(csub(v[e], p), addend[e], p);
+      } else if constexpr (kLast) {
+#pragma unroll
+        for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = csub(v[e], p);
+      } else {
+#pragma unroll
+        for (int e = 0; e < NET; ++e) lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
       }
     }
   }

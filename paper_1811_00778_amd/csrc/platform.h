@@ -38,6 +38,31 @@ struct alignas(16) U4 { uint32_t x, y, z, w; };
 typedef uint4 U4;
 #endif
 
+// ldc(table, i): element i of a read-only table (moduli, twiddles, base-conversion constants).
+// In device code the words are read through the constant address space: with a wave-uniform
+// index the compiler then issues scalar loads instead of one vector load per lane.  The tables
+// are written once, before any kernel runs, and never by a kernel.
+#if defined(__HIP_DEVICE_COMPILE__)
+template <class T>
+__device__ __forceinline__ T ldc(const T* table, size_t i) {
+  static_assert(sizeof(T) % 4 == 0 && alignof(T) >= 4, "tables are made of 32-bit words");
+  typedef const uint32_t __attribute__((address_space(4))) * cptr;
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+  cptr w = (cptr)(table + i);
+#pragma clang diagnostic pop
+  T out;
+  uint32_t* o = reinterpret_cast<uint32_t*>(&out);
+#pragma unroll
+  for (unsigned k = 0; k < sizeof(T) / 4; ++k) o[k] = w[k];
+  return out;
+}
+#elif defined(HCNN_HOSTEMU)
+template <class T> inline T ldc(const T* table, size_t i) { return table[i]; }
+#else
+template <class T> __device__ __forceinline__ T ldc(const T* table, size_t i) { return table[i]; }
+#endif
+
 #ifdef HCNN_HOSTEMU
 // ------------------------------------------------------------------ host emulation
 inline int dev_malloc(void** p, size_t bytes) {
