@@ -169,9 +169,9 @@ int hcnn_get_stat(hcnn_ctx* ctx, int which, uint64_t* out);
 int hcnn_reset_stats(hcnn_ctx* ctx);
 
 enum {
-  HCNN_OPT_AMBIGUITY_BAND = 0,  /* width (in units of 2^-31 of the modulus) of the band around
+  HCNN_OPT_AMBIGUITY_BAND = 0,  /* width (in units of 2^-26 of the modulus) of the band around
                                    the rounding boundary inside which the exact comparison is
-                                   used; 128 (default) .. 2^31 (always); raising it only costs
+                                   used; 128 (default) .. 2^26 (always); raising it only costs
                                    time (for tests) */
   HCNN_OPT_SQUARE_CHUNK = 1,    /* ciphertexts per internal batch of hcnn_ct_square_relin;
                                    0 = choose from the scratch budget */

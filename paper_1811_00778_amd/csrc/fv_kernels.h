@@ -24,13 +24,13 @@ constexpr int kEwVec = 4;         // coefficients per thread where 16-byte acces
 // is one lazy 64-bit accumulation and one reduction (Vp = m' - [M]_{m'}; callers may fold
 // further constant factors into zmul, Bp and Vp).
 //
-// sum_i z_i/m_i is estimated in fixed point with 31 fractional bits: every term
-// floor(4 z_i * floor(2^61/m_i) / 2^32) is low by less than 2 units, so the estimate S
-// satisfies S <= exact*2^31 < S + 2*ks.  When frac(S/2^31 + 1/2) is within `band`
+// sum_i z_i/m_i is estimated in fixed point with 26 fractional bits: every term
+// floor(4 z_i * floor(2^56/m_i) / 2^32) is low by less than 2 units, so the estimate S
+// satisfies S <= exact*2^26 < S + 2*ks.  When frac(S/2^31 + 1/2) is within `band`
 // units of wrapping the estimate cannot decide the rounding; the decision is then taken
 // exactly by comparing the mixed-radix (Garner) digits of the non-negative lift of x
 // with those of (M-1)/2.  With the default band (128) that happens for about one
-// coefficient in 2^24.
+// coefficient in 2^19.
 // ===================================================================================
 struct BConvDev {
   uint32_t ks, kd;
@@ -44,11 +44,12 @@ struct BConvDev {
   const uint32_t* Vp;        // [kd]
 };
 
-constexpr uint32_t kFracBits = 31;
+constexpr uint32_t kFracBits = 26;
 constexpr uint32_t kFracOne = 1u << kFracBits;
 
-// Fixed-point estimate of z/m with 31 fractional bits (low by less than 2 units).
-HCNN_HD uint32_t frac31(uint32_t z, const Mod& m) { return mulhi32(z << 2, m.mu); }
+// Fixed-point estimate of z/m with 26 fractional bits (low by less than 2 units).  The sum of up
+// to 32 such terms plus one half stays below 2^32.
+HCNN_HD uint32_t frac_est(uint32_t z, const Mod& m) { return mulhi32(z << 2, m.mu >> 5); }
 
 // col[i*stride] holds the residues x_i of a non-negative integer X < M on entry; they are replaced
 // by its mixed-radix digits.  Returns 1 when X > (M-1)/2.
@@ -71,18 +72,18 @@ HCNN_HD uint32_t garner_gt_half(const BConvDev& bc, uint32_t* col, int stride) {
   return 0;
 }
 
-// Rounding decision from the estimate S (sum of frac31 terms).  `exact` is called only when the
+// Rounding decision from the estimate S (sum of frac_est terms).  `exact` is called only when the
 // estimate is not trustworthy AND the true fraction is near 1/2; it must return 1 when the
 // non-negative lift exceeds (M-1)/2.
 template <class Exact>
-HCNN_HD uint32_t bconv_round(uint64_t S, uint32_t band, Exact exact, unsigned long long* fallback_counter) {
-  const uint64_t w = S + (kFracOne >> 1);
-  uint32_t v = (uint32_t)(w >> kFracBits);
-  const uint32_t wf = (uint32_t)w & (kFracOne - 1);
+HCNN_HD uint32_t bconv_round(uint32_t S, uint32_t band, Exact exact, unsigned long long* fallback_counter) {
+  const uint32_t w = S + (kFracOne >> 1);
+  uint32_t v = w >> kFracBits;
+  const uint32_t wf = w & (kFracOne - 1);
   if (wf >= kFracOne - band) {
-    const uint32_t sf = (uint32_t)S & (kFracOne - 1);
+    const uint32_t sf = S & (kFracOne - 1);
     if (sf >= (kFracOne >> 2) && sf < 3u * (kFracOne >> 2)) {   // only then can the estimate be off
-      v = (uint32_t)(S >> kFracBits) + exact();
+      v = (S >> kFracBits) + exact();
       atomic_inc64(fallback_counter);
     }
   }
@@ -94,12 +95,12 @@ HCNN_HD uint32_t bconv_round(uint64_t S, uint32_t band, Exact exact, unsigned lo
 template <class In>
 HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32_t* gcol, int stride,
                                uint32_t band, unsigned long long* fallback_counter) {
-  uint64_t S = 0;
+  uint32_t S = 0;
   for (uint32_t i = 0; i < bc.ks; ++i) {
     const Mod m = ldc(bc.src_mod, i);
     const uint32_t z = shoup_mul(in(i), ldc(bc.zmul, i), m.p);
     zcol[i * stride] = z;
-    S += frac31(z, m);
+    S += frac_est(z, m);
   }
   auto exact = [&]() {
     for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), ldc(bc.xmul, i), ldc(bc.src_mod, i).p);
@@ -170,14 +171,14 @@ struct ExtKernelT {
     const uint32_t* src = a.in + poly * K * n + c;
     uint32_t* dst = a.out + poly * (size_t)(K + KP) * n + c;
     uint32_t x[K], z[K];
-    uint64_t S = 0;
+    uint32_t S = 0;
 #pragma unroll
     for (int i = 0; i < K; ++i) x[i] = src[(size_t)i * n];
 #pragma unroll
     for (int i = 0; i < K; ++i) {
       const Mod m = ldc(a.bc.src_mod, i);
       z[i] = shoup_mul(x[i], ldc(a.bc.zmul, i), m.p);
-      S += frac31(z[i], m);
+      S += frac_est(z[i], m);
     }
     auto exact = [&]() {
       uint32_t* col = lds + tid;
@@ -273,12 +274,12 @@ struct ScaleKernelT {
 #pragma unroll
     for (int j = 0; j < KP; ++j) dp[j] = src[(size_t)(K + j) * n];
     // ---- r = [t d]_q  ->  y mod p
-    uint64_t S = 0;
+    uint32_t S = 0;
 #pragma unroll
     for (int i = 0; i < K; ++i) {
       const Mod m = ldc(a.to_p.src_mod, i);
       z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m.p);
-      S += frac31(z[i], m);
+      S += frac_est(z[i], m);
     }
     auto exact_q = [&]() {
 #pragma unroll
@@ -295,19 +296,22 @@ struct ScaleKernelT {
         acc += (uint64_t)z[i] * ldc(a.to_p.Bp, i * KP + j);
         if ((i & 7) == 7 && i + 1 < K) acc = reduce64(acc, dm);
       }
-      y[j] = reduce64(acc, dm);
+      y[j] = reduce64_lazy(acc, dm);          // [0, 4p): its only fast-path consumer is a Shoup product
     }
     // ---- y mod p  ->  y mod q
-    uint64_t S2 = 0;
+    uint32_t S2 = 0;
 #pragma unroll
     for (int j = 0; j < KP; ++j) {
       const Mod m = ldc(a.to_q.src_mod, j);
-      z[j < (K > KP ? K : KP) ? j : 0] = shoup_mul(y[j], ldc(a.to_q.zmul, j), m.p);
-      S2 += frac31(z[j], m);
+      z[j] = shoup_mul(y[j], ldc(a.to_q.zmul, j), m.p);
+      S2 += frac_est(z[j], m);
     }
     auto exact_p = [&]() {
 #pragma unroll
-      for (int j = 0; j < KP; ++j) col[j * kThreads] = y[j];
+      for (int j = 0; j < KP; ++j) {
+        const uint32_t pj = ldc(a.to_q.src_mod, j).p;
+        col[j * kThreads] = csub(csub(y[j], 2 * pj), pj);
+      }
       return garner_gt_half(a.to_q, col, kThreads);
     };
     const uint32_t v2 = bconv_round(S2, a.band, exact_p, a.fallback_counter);
@@ -495,23 +499,27 @@ struct MacKernel {
       int64_t s[FT][4];
 #pragma unroll
       for (int f = 0; f < FT; ++f) { s[f][0] = 0; s[f][1] = 0; s[f][2] = 0; s[f][3] = 0; }
-      uint32_t since = 0;
-      for (uint32_t tau = 0; tau < a.T; ++tau) {
-        const U4 x = *reinterpret_cast<const U4*>(in + (size_t)l_idx[tau] * ct_words);
-#pragma unroll
-        for (int f = 0; f < FT; ++f) {
-          const int32_t wf = l_w[(size_t)f * a.T + tau];
-          // residues are below 2^30, so they are valid signed 32-bit operands: one 32x32+64 multiply-add each
-          s[f][0] += (int64_t)wf * (int64_t)(int32_t)x.x;
-          s[f][1] += (int64_t)wf * (int64_t)(int32_t)x.y;
-          s[f][2] += (int64_t)wf * (int64_t)(int32_t)x.z;
-          s[f][3] += (int64_t)wf * (int64_t)(int32_t)x.w;
-        }
-        if (++since == a.chunk) {
-          since = 0;
+      // terms are consumed in runs of at most `chunk` (partial sums stay below 2^63 inside a run);
+      // the inner loop is branch-free so that the loads of several terms are in flight together
+      for (uint32_t t0 = 0; t0 < a.T; t0 += a.chunk) {
+        const uint32_t t1 = t0 + a.chunk < a.T ? t0 + a.chunk : a.T;
+        if (t0 != 0) {
 #pragma unroll
           for (int f = 0; f < FT; ++f)
             for (int q = 0; q < 4; ++q) s[f][q] = fold(s[f][q], m);
+        }
+#pragma unroll 4
+        for (uint32_t tau = t0; tau < t1; ++tau) {
+          const U4 x = *reinterpret_cast<const U4*>(in + (size_t)l_idx[tau] * ct_words);
+#pragma unroll
+          for (int f = 0; f < FT; ++f) {
+            const int32_t wf = l_w[(size_t)f * a.T + tau];
+            // residues are below 2^30, so they are valid signed 32-bit operands: one 32x32+64 multiply-add each
+            s[f][0] += (int64_t)wf * (int64_t)(int32_t)x.x;
+            s[f][1] += (int64_t)wf * (int64_t)(int32_t)x.y;
+            s[f][2] += (int64_t)wf * (int64_t)(int32_t)x.z;
+            s[f][3] += (int64_t)wf * (int64_t)(int32_t)x.w;
+          }
         }
       }
 #pragma unroll

@@ -874,7 +874,7 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
   switch (which) {
     case HCNN_OPT_AMBIGUITY_BAND:
       // never below the error bound 2*ks of the estimate, at most "always ask the exact comparison"
-      if (value < 4ull * HCNN_MAX_LIMBS || value > (1ull << 31)) return HCNN_ERR_ARG;
+      if (value < 4ull * HCNN_MAX_LIMBS || value > (1ull << 26)) return HCNN_ERR_ARG;
       c->band = (uint32_t)value;
       return HCNN_OK;
     case HCNN_OPT_SQUARE_CHUNK:

@@ -192,7 +192,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
     if chunk:
         s.ctx.set_square_chunk(chunk)
     if force_exact:
-        s.ctx.set_ambiguity_band(2 ** 31)
+        s.ctx.set_ambiguity_band(2 ** 26)
     out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
     want = np.stack([fv.square_relin(s.octx, cts[i], s.evk) for i in range(len(cts))])
     assert np.array_equal(out, want), ("square_relin", n, k)
