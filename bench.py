@@ -28,6 +28,58 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 ALU_PEAK_TOPS = 39.3           # 256 CU x 64 lanes x 2.4 GHz 32-bit integer VALU instructions / s
 
 
+def time_layer(cid, torch, binding, layers, gen, reps=3):
+    """One conv layer + square activation at the shape of configuration `cid`: ms for the scalar MAC,
+    ms for the squarings, compulsory-traffic bandwidth of the MAC.  Inputs are uniformly random residues
+    generated on the device (timing does not depend on the values)."""
+    cfg = gen.CONFIGS[cid]
+    n, k, t = cfg["n"], cfg["k"], cfg["t"]
+    fc = cfg.get("fc")
+    cv = cfg.get("conv") or dict(c_in=fc["n_in"], h=1, w=1, filters=fc["n_out"], fh=1, fw=1, stride=1,
+                                 w_bound=fc["w_bound"])          # a fully connected layer is a 1x1 "image"
+    q, p = binding.choose_moduli(n, k, t)
+    ctx = binding.Context(n, q, p, t, device="cuda:0")
+    rng = gen.rng_for(cid, 1)
+    kr = gen.key_randomness(rng, q, n)
+    dev = ctx.to_device
+    _, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
+    ctx.set_relin_key(evk)
+    n_in = cv["c_in"] * cv["h"] * cv["w"]
+    gtorch = torch.Generator(device=ctx.device)
+    gtorch.manual_seed(gen.SEED_BASE + cid)
+    cts = torch.randint(0, 1 << 29, (n_in, 2, k, n), dtype=torch.int32, device=ctx.device, generator=gtorch)
+    idx_h, _, (ho, wo) = layers.conv_index_table(cv["c_in"], cv["h"], cv["w"], cv["fh"], cv["fw"], cv["stride"])
+    F, G = cv["filters"], idx_h.shape[0]
+    w_h = layers.conv_weight_table(gen.int_weights(rng, (F, cv["c_in"], cv["fh"], cv["fw"]), cv["w_bound"]), G)
+    idx, w = dev(idx_h), dev(w_h)
+    mac_out = torch.empty((F, G, 2, k, n), dtype=torch.int32, device=ctx.device)
+    flat = mac_out.reshape((F * G, 2, k, n))
+    if fc:                                        # deep-modulus configuration: square the stated batch instead
+        flat = cts[:cfg["n_square"]]
+    sq_out = torch.empty_like(flat)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    mac_ms, sq_ms = [], []
+    for r in range(reps + 1):
+        ev[0].record()
+        ctx.ct_scalar_mac(cts, idx, w, cv["w_bound"], out=mac_out)
+        ev[1].record()
+        ctx.ct_square_relin(flat, out=sq_out)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if r:                                     # first repetition warms up (scratch allocation)
+            mac_ms.append(ev[0].elapsed_time(ev[1]))
+            sq_ms.append(ev[1].elapsed_time(ev[2]))
+    ctx.close()
+    ct_bytes = 2 * k * n * 4
+    mac = sorted(mac_ms)[len(mac_ms) // 2]
+    sq = sorted(sq_ms)[len(sq_ms) // 2]
+    return dict(n=n, k=k, inputs=n_in, outputs=F * G, terms=int(idx_h.shape[1]),
+                mac_ms=round(mac, 4), square_relin_ms=round(sq, 4), layer_ms=round(mac + sq, 4),
+                mac_compulsory_GBps=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9, 1),
+                mac_hbm_frac=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                squarings=int(flat.shape[0]), squarings_per_s=round(flat.shape[0] / (sq * 1e-3), 1))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,6 +88,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=3, help="squarings the oracle computes for cpu_baseline")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
+    ap.add_argument("--no-layers", action="store_true", help="skip the conv-layer timings (configs 3 and 4)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain device copy of 256 MiB (a reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -145,6 +198,13 @@ def main():
             extra["scalar_mac_GBps_compulsory"] = round(mac_bytes * kk_["launches"] / (kk_["total_ms"] * 1e-3) / 1e9, 1)
         roofline["other_kernels"] = extra
 
+    # ---- the layer-shaped workloads of the metric ("encrypted conv layer ms"): scalar MAC + square
+    #      activation on MNIST- and CIFAR-10-shaped layers, random ciphertexts resident in HBM
+    layers_out = {}
+    if not args.no_layers:
+        for cid in (3, 4, 5):
+            layers_out[gen.CONFIGS[cid]["name"]] = time_layer(cid, torch, binding, layers, gen)
+
     # ---- CPU oracle on a bounded sample of the same squarings (also a parity check)
     cpu = None
     if not args.no_cpu_baseline:
@@ -182,6 +242,7 @@ def main():
                    "n": n, "k": k, "k_aux": len(p), "batch": n_ct},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "conv_layers": layers_out,
         "kernels": kernels,
         "profiled_pass_ms_per_step": None if elapsed_prof is None else round(elapsed_prof * 1e3 / args.steps, 4),
         "exact_rounding_fallbacks": fallbacks,

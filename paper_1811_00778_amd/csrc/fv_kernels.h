@@ -10,6 +10,7 @@ namespace hcnn {
 
 constexpr int kEwThreads = 256;   // threads per workgroup of the element-wise kernels
 constexpr int kEwVec = 4;         // coefficients per thread where 16-byte accesses are used
+constexpr uint32_t kXcds = 8;     // accelerator dies (each with its own L2); workgroup i runs on die i % 8
 
 // ===================================================================================
 // Exact centred base conversion.
@@ -452,43 +453,56 @@ struct MacKernelDirect {
 };
 
 // Main variant: the gather row and the F*T weights of the group are staged in LDS once per
-// workgroup (validated while staging: a bad index or weight becomes a zero-weight term on input 0),
-// so the term loop reads them with broadcast LDS reads and carries no branches.
+// workgroup (validated while staging: a bad index or weight becomes a zero-weight term on input 0;
+// the row is padded with such terms to a multiple of kMacBatch), so the term loop reads them with
+// broadcast LDS reads and carries no data-dependent branches.  Inputs are fetched kMacBatch terms
+// ahead of their use (double buffering in registers) to keep HBM requests in flight during the
+// multiply-adds.  Requires chunk % kMacBatch == 0.
+constexpr uint32_t kMacBatch = 4;
 template <int FT>
 struct MacKernel {
   static constexpr int kThreads = kEwThreads;
   static constexpr int kPhases = 2;
   struct Regs {};
-  static size_t lds_bytes(size_t F, size_t T) { return (1 + F) * T * 4; }
-  HCNN_HD static int64_t fold(int64_t s, const Mod& m) { return MacKernelDirect<FT>::fold(s, m); }
+  static size_t padded_terms(size_t T) { return (T + kMacBatch - 1) / kMacBatch * kMacBatch; }
+  static size_t lds_bytes(size_t F, size_t T) { return (1 + F) * padded_terms(T) * 4; }
+  static size_t grid(size_t tiles, size_t G) { return kXcds * ((tiles + kXcds - 1) / kXcds) * G; }
   template <int PH>
   HCNN_HD static void phase(const MacArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
     const uint32_t ct_words32 = 2u * a.k * a.n;                       // at most 2^22
     const size_t ct_words = ct_words32;
     const uint32_t tiles = ct_words32 / (kThreads * kEwVec);
-    const uint32_t g = bid / tiles;
-    const uint32_t tile = bid % tiles;
-    uint32_t* l_idx = lds;                                            // [T]
-    int32_t* l_w = reinterpret_cast<int32_t*>(lds + a.T);             // [F][T]
+    // Workgroups go to the 8 XCDs round-robin by index, and each XCD has its own L2.  XCD x sweeps
+    // the coefficient tiles x, x+8, ... and, inside a tile, the groups in order: the blocks that are
+    // resident on one XCD at a time then share their gather rows' inputs (neighbouring filter
+    // placements overlap), so every input tile is fetched from HBM about once.
+    const uint32_t xcd = bid % kXcds, local = bid / kXcds;
+    const uint32_t tile = (local / a.G) * kXcds + xcd;
+    const uint32_t g = local % a.G;
+    if (tile >= tiles) return;                                        // padding blocks (whole block)
+    const uint32_t Tpad = (a.T + kMacBatch - 1) / kMacBatch * kMacBatch;
+    uint32_t* l_idx = lds;                                            // [Tpad]
+    int32_t* l_w = reinterpret_cast<int32_t*>(lds + Tpad);            // [F][Tpad]
     if constexpr (PH == 0) {
       const uint32_t* idx = a.idx + (size_t)g * a.T;
       const int32_t* w = a.w + (size_t)g * a.F * a.T;
-      for (uint32_t tau = tid; tau < a.T; tau += kThreads) {
-        uint32_t src = idx[tau];
+      for (uint32_t tau = tid; tau < Tpad; tau += kThreads) {
+        const bool pad = tau >= a.T;
+        uint32_t src = pad ? 0u : idx[tau];
         const bool bad_src = src >= a.n_in;
         if (bad_src) {
           src = 0;
           if (tile == 0) atomic_inc64(a.bad_counter);
         }
-        l_idx[tau] = src;
+        l_idx[tau] = src * ct_words32;       // word offset of the input (the host checked that it fits)
 #pragma unroll
         for (int f = 0; f < FT; ++f) {
-          int32_t wf = w[(size_t)f * a.T + tau];
+          int32_t wf = pad ? 0 : w[(size_t)f * a.T + tau];
           if (wf > a.w_abs_max || wf < -a.w_abs_max) {
             wf = 0;
             if (tile == 0) atomic_inc64(a.bad_counter);
           }
-          l_w[(size_t)f * a.T + tau] = bad_src ? 0 : wf;
+          l_w[(size_t)f * Tpad + tau] = bad_src ? 0 : wf;
         }
       }
     } else {
@@ -496,37 +510,58 @@ struct MacKernel {
       const uint32_t row = tile / (a.n / (kThreads * kEwVec));        // (poly, limb) row; uniform in the block
       const Mod m = ldc(a.mods, row % a.k);
       const uint32_t* in = a.in + pos;
-      int64_t s[FT][4];
+      // accumulators carry the bias p*2^33 (a multiple of p above 2^62), so they stay positive while
+      // the signed partial sums stay inside (-2^62, 2^62) and one unsigned reduction folds them
+      const uint64_t bias = (uint64_t)m.p << 33;
+      uint64_t s[FT][4];
 #pragma unroll
-      for (int f = 0; f < FT; ++f) { s[f][0] = 0; s[f][1] = 0; s[f][2] = 0; s[f][3] = 0; }
-      // terms are consumed in runs of at most `chunk` (partial sums stay below 2^63 inside a run);
-      // the inner loop is branch-free so that the loads of several terms are in flight together
-      for (uint32_t t0 = 0; t0 < a.T; t0 += a.chunk) {
-        const uint32_t t1 = t0 + a.chunk < a.T ? t0 + a.chunk : a.T;
-        if (t0 != 0) {
+      for (int f = 0; f < FT; ++f) { s[f][0] = bias; s[f][1] = bias; s[f][2] = bias; s[f][3] = bias; }
+      auto fetch = [&](U4 (&buf)[kMacBatch], uint32_t t) {
 #pragma unroll
-          for (int f = 0; f < FT; ++f)
-            for (int q = 0; q < 4; ++q) s[f][q] = fold(s[f][q], m);
-        }
-#pragma unroll 4
-        for (uint32_t tau = t0; tau < t1; ++tau) {
-          const U4 x = *reinterpret_cast<const U4*>(in + (size_t)l_idx[tau] * ct_words);
+        for (uint32_t b = 0; b < kMacBatch; ++b)
+          buf[b] = *reinterpret_cast<const U4*>(in + (size_t)l_idx[t + b]);     // l_idx holds word offsets
+      };
+      auto consume = [&](const U4 (&buf)[kMacBatch], uint32_t t) {
+#pragma unroll
+        for (uint32_t b = 0; b < kMacBatch; ++b) {
 #pragma unroll
           for (int f = 0; f < FT; ++f) {
-            const int32_t wf = l_w[(size_t)f * a.T + tau];
+            const int64_t wf = l_w[(size_t)f * Tpad + t + b];
             // residues are below 2^30, so they are valid signed 32-bit operands: one 32x32+64 multiply-add each
-            s[f][0] += (int64_t)wf * (int64_t)(int32_t)x.x;
-            s[f][1] += (int64_t)wf * (int64_t)(int32_t)x.y;
-            s[f][2] += (int64_t)wf * (int64_t)(int32_t)x.z;
-            s[f][3] += (int64_t)wf * (int64_t)(int32_t)x.w;
+            s[f][0] += (uint64_t)(wf * (int64_t)(int32_t)buf[b].x);
+            s[f][1] += (uint64_t)(wf * (int64_t)(int32_t)buf[b].y);
+            s[f][2] += (uint64_t)(wf * (int64_t)(int32_t)buf[b].z);
+            s[f][3] += (uint64_t)(wf * (int64_t)(int32_t)buf[b].w);
           }
+        }
+      };
+      auto refold = [&]() {
+#pragma unroll
+        for (int f = 0; f < FT; ++f)
+          for (int q = 0; q < 4; ++q) s[f][q] = bias + reduce64(s[f][q], m);
+      };
+      // two register buffers used alternately: the loads of the next batch are in flight while the
+      // current one is consumed
+      U4 buf_a[kMacBatch], buf_b[kMacBatch];
+      fetch(buf_a, 0);
+      uint32_t since = 0;
+      for (uint32_t tau = 0; tau < Tpad; tau += 2 * kMacBatch) {
+        if (tau + kMacBatch < Tpad) fetch(buf_b, tau + kMacBatch);
+        if (since >= a.chunk) { since = 0; refold(); }
+        since += kMacBatch;
+        consume(buf_a, tau);
+        if (tau + kMacBatch < Tpad) {
+          if (tau + 2 * kMacBatch < Tpad) fetch(buf_a, tau + 2 * kMacBatch);
+          if (since >= a.chunk) { since = 0; refold(); }
+          since += kMacBatch;
+          consume(buf_b, tau + kMacBatch);
         }
       }
 #pragma unroll
       for (int f = 0; f < FT; ++f) {
         U4 r;
-        r.x = (uint32_t)fold(s[f][0], m); r.y = (uint32_t)fold(s[f][1], m);
-        r.z = (uint32_t)fold(s[f][2], m); r.w = (uint32_t)fold(s[f][3], m);
+        r.x = reduce64(s[f][0], m); r.y = reduce64(s[f][1], m);
+        r.z = reduce64(s[f][2], m); r.w = reduce64(s[f][3], m);
         *reinterpret_cast<U4*>(a.out + ((size_t)f * a.G + g) * ct_words + pos) = r;
       }
     }

@@ -482,7 +482,13 @@ int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
 template <int FT>
 int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
   const size_t lds = MacKernel<FT>::lds_bytes(a.F, a.T);
-  if (lds <= 64 * 1024 && lds <= c->max_lds) return run<MacKernel<FT>>(c, grid, lds, a);
+  const size_t tiles = grid / a.G;
+  const bool offsets_fit = (uint64_t)a.n_in * 2 * a.k * a.n <= 0xffffffffull;   // word offsets kept in 32 bits
+  if (lds <= 64 * 1024 && lds <= c->max_lds && a.chunk >= kMacBatch && offsets_fit) {
+    MacArgs b = a;
+    b.chunk = a.chunk / kMacBatch * kMacBatch;      // the staged kernel reduces at batch boundaries
+    return run<MacKernel<FT>>(c, MacKernel<FT>::grid(tiles, a.G), lds, b);
+  }
   return run<MacKernelDirect<FT>>(c, grid, 0, a);
 }
 
@@ -649,9 +655,9 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
   a.mods = c->d_mods; a.k = c->k; a.n = c->n;
   a.n_in = (uint32_t)n_in; a.G = (uint32_t)G; a.F = (uint32_t)F; a.T = (uint32_t)T;
   a.w_abs_max = w_abs_max;
-  // partial sums stay below 2^63: chunk * w_abs_max * 2^30 + 2^30 <= 2^63
+  // partial sums stay below 2^62 in magnitude: chunk * w_abs_max * 2^30 + 2^30 <= 2^62
   const uint64_t wm = w_abs_max > 0 ? (uint64_t)w_abs_max : 1;
-  uint64_t chunk = ((1ull << 33) - 1) / wm;
+  uint64_t chunk = ((1ull << 32) - 1) / wm;
   if (chunk > T) chunk = T;
   a.chunk = (uint32_t)chunk;
   a.bad_counter = c->d_counters + 1;

@@ -122,12 +122,18 @@ def check_scalar_mac(backend, n, k, seed_id=1):
     # T = 1, F = 1 and F = 16
     run(idx[:, :1].copy(), gen.int_weights(s.rng, (3, 1, 1), 8), 8)
     run(idx[:1].copy(), gen.int_weights(s.rng, (1, 16, 7), 31), 31)
-    # extreme weights force intermediate reductions of the partial sums (4 terms per reduction)
+    # extreme weights force intermediate reductions of the partial sums (2 terms per reduction)
     big = 2 ** 31 - 1
     w = gen.int_weights(s.rng, (2, 2, 7), big)
     w[0, 0, :] = big
     w[0, 1, :] = -big
     run(idx[:2].copy(), w, big)
+    # large (not extreme) weights: the staged kernel reduces its partial sums every 4 terms
+    mid = 2 ** 29
+    idx40 = s.rng.integers(0, n_in, size=(2, 41)).astype(np.uint32)
+    w40 = gen.int_weights(s.rng, (2, 3, 41), mid)
+    w40[1, 2, :] = -mid
+    run(idx40, w40, mid)
     # a gather row too long for the LDS-staged kernel takes the direct variant ((1+F)*T*4 > 64 KiB)
     long_idx = s.rng.integers(0, n_in, size=(1, 5000)).astype(np.uint32)
     run(long_idx, gen.int_weights(s.rng, (1, 3, 5000), 100), 100)
