@@ -42,6 +42,7 @@ struct BConvDev {
   const uint32_t* half;      // [ks]   mixed-radix digits of (M-1)/2
   const Mod* dst_mod;        // [kd]
   const uint32_t* Bp;        // [ks][kd]
+  const uint32_t* BpT;       // [kd][ks]  the same constants, transposed
   const uint32_t* Vp;        // [kd]
 };
 
@@ -251,11 +252,14 @@ struct ScaleKernel {
   }
 };
 
-// Register-resident variant (see ExtKernelT).
+// Register-resident variant (see ExtKernelT) with a rolled loop over the auxiliary primes: y_j is produced, used at once for the
+// p -> q conversion (k running 64-bit sums) and parked in the LDS column for the exact path, so
+// the register footprint is 3k + O(1) and the code size does not grow with k*k'.
 template <int K, int KP>
-struct ScaleKernelT {
+struct ScaleKernelR {
   static constexpr int kThreads = kEwThreads;
   static constexpr int kPhases = 1;
+  static constexpr int kCadence = 14;      // products below 2^60 that fit a 64-bit sum with room to spare
   struct Regs {};
   static size_t lds_bytes() { return (size_t)(K > KP ? K : KP) * kThreads * 4; }
   template <int PH>
@@ -269,63 +273,63 @@ struct ScaleKernelT {
     uint32_t* dst = a.y + poly * (size_t)K * n + c;
     uint32_t* col = lds + tid;
 
-    uint32_t dq[K], dp[KP], z[K > KP ? K : KP], y[KP];
-#pragma unroll
-    for (int i = 0; i < K; ++i) dq[i] = src[(size_t)i * n];
-#pragma unroll
-    for (int j = 0; j < KP; ++j) dp[j] = src[(size_t)(K + j) * n];
-    // ---- r = [t d]_q  ->  y mod p
+    uint32_t z[K];
     uint32_t S = 0;
+    {
+      uint32_t dq[K];
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-      const Mod m = ldc(a.to_p.src_mod, i);
-      z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m.p);
-      S += frac_est(z[i], m);
+      for (int i = 0; i < K; ++i) dq[i] = src[(size_t)i * n];
+#pragma unroll
+      for (int i = 0; i < K; ++i) {
+        const Mod m = ldc(a.to_p.src_mod, i);
+        z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m.p);
+        S += frac_est(z[i], m);
+      }
     }
     auto exact_q = [&]() {
-#pragma unroll
-      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(dq[i], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i).p);
+      for (uint32_t i = 0; i < (uint32_t)K; ++i)
+        col[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i).p);
       return garner_gt_half(a.to_p, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact_q, a.fallback_counter);
+
+    uint64_t out_acc[K];
 #pragma unroll
-    for (int j = 0; j < KP; ++j) {
+    for (int i = 0; i < K; ++i) out_acc[i] = 0;
+    uint32_t S2 = 0;
+    uint32_t dp_next = src[(size_t)K * n];
+#pragma unroll 1
+    for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
+      const uint32_t dpj = dp_next;
+      if (j + 1 < (uint32_t)KP) dp_next = src[(size_t)(K + j + 1) * n];
       const Mod dm = ldc(a.to_p.dst_mod, j);
-      uint64_t acc = (uint64_t)dp[j] * ldc(a.tq_inv, j) + (uint64_t)v * ldc(a.to_p.Vp, j);
+      uint64_t acc = (uint64_t)dpj * ldc(a.tq_inv, j) + (uint64_t)v * ldc(a.to_p.Vp, j);
+      const uint32_t* bt = a.to_p.BpT + (size_t)j * K;
 #pragma unroll
       for (int i = 0; i < K; ++i) {
-        acc += (uint64_t)z[i] * ldc(a.to_p.Bp, i * KP + j);
-        if ((i & 7) == 7 && i + 1 < K) acc = reduce64(acc, dm);
+        acc += (uint64_t)z[i] * ldc(bt, i);
+        if ((i % kCadence) == kCadence - 2 && i + 1 < K) acc = reduce64(acc, dm);   // two extra terms came first
       }
-      y[j] = reduce64_lazy(acc, dm);          // [0, 4p): its only fast-path consumer is a Shoup product
-    }
-    // ---- y mod p  ->  y mod q
-    uint32_t S2 = 0;
+      const uint32_t yj = reduce64(acc, dm);
+      col[j * kThreads] = yj;
+      const Mod sm = ldc(a.to_q.src_mod, j);
+      const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm.p);
+      S2 += frac_est(z2, sm);
+      const uint32_t* b2 = a.to_q.Bp + (size_t)j * K;
 #pragma unroll
-    for (int j = 0; j < KP; ++j) {
-      const Mod m = ldc(a.to_q.src_mod, j);
-      z[j] = shoup_mul(y[j], ldc(a.to_q.zmul, j), m.p);
-      S2 += frac_est(z[j], m);
-    }
-    auto exact_p = [&]() {
+      for (int i = 0; i < K; ++i) out_acc[i] += (uint64_t)z2 * ldc(b2, i);
+      if ((j % kCadence) == kCadence - 1) {
 #pragma unroll
-      for (int j = 0; j < KP; ++j) {
-        const uint32_t pj = ldc(a.to_q.src_mod, j).p;
-        col[j * kThreads] = csub(csub(y[j], 2 * pj), pj);
+        for (int i = 0; i < K; ++i) out_acc[i] = reduce64(out_acc[i], ldc(a.to_q.dst_mod, i));
       }
-      return garner_gt_half(a.to_q, col, kThreads);
-    };
+    }
+    auto exact_p = [&]() { return garner_gt_half(a.to_q, col, kThreads); };
     const uint32_t v2 = bconv_round(S2, a.band, exact_p, a.fallback_counter);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
       const Mod dm = ldc(a.to_q.dst_mod, i);
-      uint64_t acc = (uint64_t)v2 * ldc(a.to_q.Vp, i);
-#pragma unroll
-      for (int j = 0; j < KP; ++j) {
-        acc += (uint64_t)z[j] * ldc(a.to_q.Bp, j * K + i);
-        if ((j & 7) == 7 && j + 1 < KP) acc = reduce64(acc, dm);
-      }
-      dst[(size_t)i * n] = reduce64(acc, dm);
+      // at most kCadence-1 products since the last reduction, plus a residue, plus v2*Vp < 2^35
+      dst[(size_t)i * n] = reduce64(out_acc[i] + (uint64_t)v2 * ldc(a.to_q.Vp, i), dm);
     }
   }
 };

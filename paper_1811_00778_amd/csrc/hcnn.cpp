@@ -154,7 +154,7 @@ struct BConvHost {
   uint32_t ks = 0, kd = 0;
   std::vector<Mod> src_mod, dst_mod;
   std::vector<ShoupConst> zmul, xmul;
-  std::vector<uint32_t> ginv, half, Bp, Vp;
+  std::vector<uint32_t> ginv, half, Bp, BpT, Vp;
 };
 
 struct hcnn_ctx {
@@ -214,7 +214,7 @@ template <int A, int B, int C> struct KernelClass<NttFwd<A, B, C>> { static cons
 template <int A, int B, int C> struct KernelClass<NttInv<A, B, C>> { static constexpr int id = HCNN_PROF_NTT_INV; };
 template <> struct KernelClass<ExtKernel> { static constexpr int id = HCNN_PROF_BASE_EXT; };
 template <int A, int B> struct KernelClass<ExtKernelT<A, B>> { static constexpr int id = HCNN_PROF_BASE_EXT; };
-template <int A, int B> struct KernelClass<ScaleKernelT<A, B>> { static constexpr int id = HCNN_PROF_SCALE; };
+template <int A, int B> struct KernelClass<ScaleKernelR<A, B>> { static constexpr int id = HCNN_PROF_SCALE; };
 template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
 template <> struct KernelClass<RelinMacKernel> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
 template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
@@ -303,12 +303,15 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
       h.Bp[(size_t)i * h.kd + j] = fold_inv ? mj - h_inv(src[i] % mj, mj) : h_prod_mod(src, (int)i, mj);
     h.Vp[j] = fold_inv ? 1u : (mj - h_prod_mod(src, -1, mj)) % mj;
   }
+  h.BpT.assign((size_t)h.ks * h.kd, 0);
+  for (uint32_t i = 0; i < h.ks; ++i)
+    for (uint32_t j = 0; j < h.kd; ++j) h.BpT[(size_t)j * h.ks + i] = h.Bp[(size_t)i * h.kd + j];
   return h;
 }
 
 int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
   int e;
-  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* Mm;
+  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* BT; uint32_t* Mm;
   if ((e = upload(c, h.src_mod, &sm))) return e;
   if ((e = upload(c, h.dst_mod, &dm))) return e;
   if ((e = upload(c, h.zmul, &zm))) return e;
@@ -316,10 +319,11 @@ int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
   if ((e = upload(c, h.ginv, &gi))) return e;
   if ((e = upload(c, h.half, &hf))) return e;
   if ((e = upload(c, h.Bp, &B))) return e;
+  if ((e = upload(c, h.BpT, &BT))) return e;
   if ((e = upload(c, h.Vp, &Mm))) return e;
   d->ks = h.ks; d->kd = h.kd;
   d->src_mod = sm; d->dst_mod = dm; d->zmul = zm; d->xmul = xm;
-  d->ginv = gi; d->half = hf; d->Bp = B; d->Vp = Mm;
+  d->ginv = gi; d->half = hf; d->Bp = B; d->BpT = BT; d->Vp = Mm;
   return 0;
 }
 
@@ -473,7 +477,7 @@ int ext_dispatch(hcnn_ctx* c, size_t grid, const ExtArgs& a) {
 int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_SCALE_CASE(K, KP) \
-  if (k == K && kp == KP) return run<ScaleKernelT<K, KP>>(c, grid, ScaleKernelT<K, KP>::lds_bytes(), a);
+  if (k == K && kp == KP) return run<ScaleKernelR<K, KP>>(c, grid, ScaleKernelR<K, KP>::lds_bytes(), a);
   HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
 #undef HCNN_SCALE_CASE
   return run<ScaleKernel>(c, grid, ScaleKernel::lds_bytes(k, kp), a);
@@ -677,7 +681,7 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
   const size_t words_per_ct = ((size_t)2 * L + 3 * L + 3 * k + (size_t)k * k + 2 * k) * rn;
   size_t C = c->square_chunk;
   if (C == 0) {
-    const size_t budget = (size_t)3 << 29;   // 1.5 GiB of scratch
+    const size_t budget = (size_t)6 << 30;   // 6 GiB of scratch (of 288 GB): enough rows per launch at every n
     C = budget / (words_per_ct * 4);
     if (C > 256) C = 256;
   }
