@@ -47,6 +47,29 @@ def conv_weight_table(weights, n_groups, valid=None):
     return w
 
 
+def pool_index_table(channels, h, w, extent, stride=None):
+    """Average pooling as the paper evaluates it (Sec. 4.3): a convolution with all-ones weights per
+    channel (the division by the window size is folded into the layer's scale factor).
+
+    Returns (idx [G][T] uint32, ones [G][1][T] int32, (h_out, w_out)); G = channels*h_out*w_out groups in
+    (channel, row, column) order -- which is the output feature-map order -- and T = extent*extent."""
+    stride = extent if stride is None else stride
+    h_out, w_out = (h - extent) // stride + 1, (w - extent) // stride + 1
+    G, T = channels * h_out * w_out, extent * extent
+    idx = np.zeros((G, T), dtype=np.uint32)
+    g = 0
+    for c in range(channels):
+        for j in range(h_out):
+            for kk in range(w_out):
+                tau = 0
+                for dy in range(extent):
+                    for dx in range(extent):
+                        idx[g, tau] = c * h * w + (j * stride + dy) * w + (kk * stride + dx)
+                        tau += 1
+                g += 1
+    return idx, np.ones((G, 1, T), dtype=np.int32), (h_out, w_out)
+
+
 def fc_index_table(n_in):
     """Fully connected layer: one group whose gather row lists every input."""
     return np.arange(n_in, dtype=np.uint32)[None, :]

@@ -68,3 +68,25 @@ def test_fc_tables():
     w = np.arange(30, dtype=np.int32).reshape(3, 10)
     assert layers.fc_index_table(10).tolist() == [list(range(10))]
     assert layers.fc_weight_table(w).shape == (1, 3, 10)
+
+
+def test_pool_table_is_all_ones_convolution_per_channel():
+    rng = np.random.default_rng(4)
+    C, h, w, e = 3, 8, 6, 2
+    x = rng.integers(0, 100, size=(C, h, w))
+    idx, ones, (ho, wo) = layers.pool_index_table(C, h, w, e)
+    assert (ho, wo) == (4, 3) and idx.shape == (C * ho * wo, e * e) and ones.min() == ones.max() == 1
+    got = np.einsum("gft,gt->g", ones, x.reshape(-1)[idx]).reshape(C, ho, wo)
+    want = x.reshape(C, ho, e, wo, e).sum(axis=(2, 4))
+    assert np.array_equal(got, want)
+    # CIFAR-10 network of the paper: 32x32x32 -> 16x16x32 -> conv -> 8x8x64 -> conv -> 4x4x128 by 2x2 pooling
+    for ch, side in ((32, 32), (64, 16), (128, 8)):
+        idx, _, (ho, wo) = layers.pool_index_table(ch, side, side, 2)
+        assert ch * ho * wo == ch * (side // 2) ** 2
+
+
+def test_padded_stride1_conv_keeps_the_feature_map_size():
+    # first layer of the paper's CIFAR-10 network: 3x3x3 filters, stride 1, padding -> 32 x 32 x 32
+    idx, valid, (ho, wo) = layers.conv_index_table(3, 32, 32, 3, 3, 1, pad=1)
+    assert (ho, wo) == (32, 32) and idx.shape == (1024, 27)
+    assert valid.sum() == 27 * 1024 - 3 * (4 * 5 + 4 * 30 * 3)        # corner and edge placements lose terms
