@@ -135,6 +135,12 @@ int hcnn_ct_scalar_mac(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_in,
 int hcnn_ct_square_relin(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_ct,
                          uint32_t* out_cts_dev);
 
+/* General HMult of Sec. 2.1 (Table "FHE primitives benchmarks", not used by the paper's networks):
+ * out_i = Relinearize(round(t/q * a_i (x) b_i)) with the tensor (c0 c0', c0 c1' + c1 c0', c1 c1') over
+ * the integers on centred lifts.  a, b, out = uint32[n_ct][2][k][n]; out may be a or b. */
+int hcnn_ct_mul_relin(hcnn_ctx* ctx, const uint32_t* a_cts_dev, const uint32_t* b_cts_dev, size_t n_ct,
+                      uint32_t* out_cts_dev);
+
 /* ---- test helpers (same kernels, not tuned) ------------------------------------------- */
 
 /* KeyGen of Sec. 2.1 with the randomness passed in:

@@ -24,6 +24,7 @@ SIGNATURES = {
     "hcnn_ntt_inv": [ptr, ptr, C.c_size_t],
     "hcnn_ct_scalar_mac": [ptr, ptr, C.c_size_t, ptr, ptr, C.c_int32, C.c_size_t, C.c_size_t, C.c_size_t, ptr],
     "hcnn_ct_square_relin": [ptr, ptr, C.c_size_t, ptr],
+    "hcnn_ct_mul_relin": [ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_keygen": [ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr],
     "hcnn_encrypt": [ptr, ptr, ptr, ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_decrypt": [ptr, ptr, ptr, C.c_size_t, ptr],

@@ -77,6 +77,18 @@ class OpsMixin:
         self.raw.call("hcnn_ct_square_relin", self._ptr(in_cts), n_ct, self._ptr(out))
         return out
 
+    def ct_mul_relin(self, a_cts, b_cts, out=None):
+        """HMult of every pair (a_i, b_i), with scaling and relinearisation (hcnn_ct_mul_relin)."""
+        self._check(a_cts, "u32"); self._check(b_cts, "u32")
+        n_ct = self._count(a_cts, self.ct_shape)
+        if tuple(b_cts.shape) != tuple(a_cts.shape):
+            raise ValueError("a and b must have the same shape")
+        if out is None:
+            out = self._empty(tuple(a_cts.shape), "u32")
+        self._check(out, "u32")
+        self.raw.call("hcnn_ct_mul_relin", self._ptr(a_cts), self._ptr(b_cts), n_ct, self._ptr(out))
+        return out
+
     # ---- test helpers
     def keygen(self, s, a, e, a_evk=None, e_evk=None):
         self._check(s, "i32"); self._check(a, "u32"); self._check(e, "i32")

@@ -437,6 +437,7 @@ int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse, int io) {
   const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;
   if (inverse) {
     if (io == kNttLoadTensor) return run<NttInv<LOGN, LOGR, kNttLoadTensor>>(c, r.rows, lds, a);
+    if (io == kNttLoadTensorMul) return run<NttInv<LOGN, LOGR, kNttLoadTensorMul>>(c, r.rows, lds, a);
     if (io == kNttStoreAdd) return run<NttInv<LOGN, LOGR, kNttStoreAdd>>(c, r.rows, lds, a);
     return run<NttInv<LOGN, LOGR>>(c, r.rows, lds, a);
   }
@@ -668,17 +669,18 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
   return mac_dispatch(c, G * tiles, a);
 }
 
-int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t* out) {
+// HMult of Sec. 2.1 on n_ct pairs (a_i, b_i); b == nullptr squares a (HSquare).
+static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b, size_t n_ct, uint32_t* out) {
   if (!c) return HCNN_ERR_NULL;
   if (n_ct == 0) return HCNN_OK;
   if (!in || !out) return HCNN_ERR_NULL;
-  if (!aligned16(in) || !aligned16(out)) return HCNN_ERR_ALIGN;
+  if (!aligned16(in) || !aligned16(out) || !aligned16(in_b)) return HCNN_ERR_ALIGN;
   if (c->kp == 0) return HCNN_ERR_AUX;
   if (!c->has_key) return HCNN_ERR_NOKEY;
-  if (n_ct == 0) return HCNN_OK;
   const uint32_t k = c->k, kp = c->kp, L = k + kp, n = c->n;
   const size_t rn = n;
-  const size_t words_per_ct = ((size_t)2 * L + 3 * L + 3 * k + (size_t)k * k + 2 * k) * rn;
+  const size_t ext_rows = in_b ? 4 * (size_t)L : 2 * (size_t)L;
+  const size_t words_per_ct = (ext_rows + 3 * L + 3 * k + (size_t)k * k + 2 * k) * rn;
   size_t C = c->square_chunk;
   if (C == 0) {
     const size_t budget = (size_t)6 << 30;   // 6 GiB of scratch (of 288 GB): enough rows per launch at every n
@@ -692,7 +694,8 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
   int e = ensure_scratch(c, C * words_per_ct * 4);
   if (e) return e;
   uint32_t* ext = c->scratch;
-  uint32_t* d = ext + C * 2 * L * rn;
+  uint32_t* ext_b = ext + C * 2 * L * rn;                 // used only by the two-operand product
+  uint32_t* d = ext + C * ext_rows * rn;
   uint32_t* y = d + C * 3 * L * rn;
   uint32_t* dig = y + C * 3 * k * rn;
   uint32_t* acc = dig + C * k * k * rn;
@@ -702,16 +705,23 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
 
   for (size_t c0 = 0; c0 < n_ct; c0 += C) {
     const size_t cc = std::min(C, n_ct - c0);
-    // 1. centred lift of c0, c1 extended to the auxiliary primes
+    // 1. centred lift of c0, c1 extended to the auxiliary primes; 2. forward NTT over all k + k' limbs
     ExtArgs ea;
     ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-    // 2. forward NTT over all k + k' limbs
     if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false))) return e;
-    // 3+4. tensor (c0^2, 2 c0 c1, c1^2) formed while loading, then back to coefficients: the integer
-    //      tensor, known mod q*p
-    if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensor))) return e;
+    if (in_b) {
+      ea.in = in_b + c0 * ct_words; ea.out = ext_b;
+      if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
+      if ((e = ntt_dense(c, ext_b, ext_b, cc * 2 * L, L, false))) return e;
+    }
+    // 3+4. tensor formed while loading, then back to coefficients: the integer tensor, known mod q*p
+    if (in_b) {
+      if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensorMul, ext_b))) return e;
+    } else {
+      if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensor))) return e;
+    }
     // 5. y = round(t/q * d) mod q
     ScaleArgs sa;
     sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
@@ -727,6 +737,15 @@ int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t*
     if ((e = ntt_dense(c, acc, out + c0 * ct_words, cc * 2 * k, k, true, kNttStoreAdd, y))) return e;
   }
   return HCNN_OK;
+}
+
+int hcnn_ct_square_relin(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t* out) {
+  return mul_relin_impl(c, in, nullptr, n_ct, out);
+}
+
+int hcnn_ct_mul_relin(hcnn_ctx* c, const uint32_t* a, const uint32_t* b, size_t n_ct, uint32_t* out) {
+  if (n_ct != 0 && c && !b) return HCNN_ERR_NULL;
+  return mul_relin_impl(c, a, b, n_ct, out);
 }
 
 // ---------------------------------------------------------------- test helpers

@@ -36,13 +36,16 @@ struct NttLimb {
 //                   lies in (2^29, 2^30)); output rows dense [ct][i][j]
 //   kNttLoadTensor  inverse only: row (ct, b, l) reads c0^ = in[(ct*2)*L + l], c1^ = in[(ct*2+1)*L + l]
 //                   and transforms c0^*c0^, 2*c0^*c1^ or c1^*c1^ for b = 0, 1, 2 (HMult step 1, c = c')
+//   kNttLoadTensorMul  inverse only: the general tensor of HMult step 1 for two different operands;
+//                   `in` holds the first, `aux` the second (same [ct][2][L][n] layout):
+//                   c0^*c0'^, c0^*c1'^ + c1^*c0'^, c1^*c1'^
 //   kNttStoreAdd    inverse only: row (ct, b, j) adds aux row (ct*3+b)*k + j (aux = y) on the way out
-enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3 };
+enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4 };
 
 struct NttArgs {
   const uint32_t* in;
   uint32_t* out;            // may equal `in`
-  const uint32_t* aux;      // kNttStoreAdd only
+  const uint32_t* aux;      // kNttStoreAdd: the addend; kNttLoadTensorMul: the second operand
   const ShoupConst* tw;     // [L][n] node table (forward or inverse)
   const NttLimb* limbs;     // [L]
   uint32_t limb_cycle;
@@ -164,7 +167,8 @@ struct NttFwd {
 // ------------------------------------------------------------------------- inverse
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttInv {
-  static_assert(IO == kNttPlain || IO == kNttLoadTensor || IO == kNttStoreAdd, "inverse NTT io mode");
+  static_assert(IO == kNttPlain || IO == kNttLoadTensor || IO == kNttStoreAdd || IO == kNttLoadTensorMul,
+                "inverse NTT io mode");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
@@ -185,12 +189,24 @@ struct NttInv {
     const uint32_t* gin;
     const uint32_t* gin2 = nullptr;       // kNttLoadTensor: the c1^ row
     uint32_t comp = 0;                    // kNttLoadTensor: tensor component b
+    const uint32_t* gmul0 = nullptr;      // kNttLoadTensorMul: rows c0^, c1^ of the first operand and
+    const uint32_t* gmul1 = nullptr;      // c0'^, c1'^ of the second
     if constexpr (IO == kNttLoadTensor) {
       const uint32_t LL = a.limb_cycle;
       const uint32_t ct = bid / (3 * LL);
       comp = (bid / LL) % 3;
       gin2 = a.in + ((size_t)(ct * 2 + 1) * LL + bid % LL) * N;     // c1^
       gin = comp == 2 ? gin2 : gin2 - (size_t)LL * N;                 // c0^ unless b = 2
+    } else if constexpr (IO == kNttLoadTensorMul) {
+      const uint32_t LL = a.limb_cycle;
+      const uint32_t ct = bid / (3 * LL);
+      comp = (bid / LL) % 3;
+      const size_t row0 = ((size_t)ct * 2 * LL + bid % LL) * N;        // component 0 of this limb
+      gmul0 = a.in + row0;
+      gmul1 = a.aux + row0;
+      // b = 0: c0*c0' ; b = 2: c1*c1' ; b = 1: c0*c1' + c1*c0'
+      gin = gmul0 + (comp == 2 ? (size_t)LL * N : 0);
+      gin2 = gmul1 + (comp == 0 ? 0 : (size_t)LL * N);
     } else {
       gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
     }
@@ -214,6 +230,18 @@ struct NttInv {
 #pragma unroll
         for (int e = 0; e < NET; e += 4) {
           U4 t = g4[e / 4];
+          if constexpr (IO == kNttLoadTensorMul) {
+            // t = c0^ (b = 0, 1) or c1^ (b = 2);  y = c0'^ (b = 0) or c1'^ (b = 1, 2)
+            const U4 y = reinterpret_cast<const U4*>(gin2 + base)[e / 4];
+            t.x = mul_mod(t.x, y.x, L.m); t.y = mul_mod(t.y, y.y, L.m);
+            t.z = mul_mod(t.z, y.z, L.m); t.w = mul_mod(t.w, y.w, L.m);
+            if (comp == 1) {                 // + c1^ * c0'^
+              const U4 u = reinterpret_cast<const U4*>(gmul0 + (size_t)a.limb_cycle * N + base)[e / 4];
+              const U4 w = reinterpret_cast<const U4*>(gmul1 + base)[e / 4];
+              t.x = add_mod(t.x, mul_mod(u.x, w.x, L.m), p); t.y = add_mod(t.y, mul_mod(u.y, w.y, L.m), p);
+              t.z = add_mod(t.z, mul_mod(u.z, w.z, L.m), p); t.w = add_mod(t.w, mul_mod(u.w, w.w, L.m), p);
+            }
+          }
           if constexpr (IO == kNttLoadTensor) {
             // gin was pointed at c0^ (b = 0, 1) or c1^ (b = 2); only b = 1 needs the second row
             U4 y = t;
@@ -229,6 +257,12 @@ struct NttInv {
         for (int e = 0; e < NET; ++e) {
           if constexpr (kFirst) {
             uint32_t t = gin[base + (uint32_t)e * TLAST];
+            if constexpr (IO == kNttLoadTensorMul) {
+              const uint32_t idx = base + (uint32_t)e * TLAST;
+              t = mul_mod(t, gin2[idx], L.m);
+              if (comp == 1)
+                t = add_mod(t, mul_mod(gmul0[(size_t)a.limb_cycle * N + idx], gmul1[idx], L.m), p);
+            }
             if constexpr (IO == kNttLoadTensor) {
               const uint32_t u = comp == 1 ? gin2[base + (uint32_t)e * TLAST] : t;
               t = mul_mod(t, u, L.m);

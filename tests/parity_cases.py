@@ -214,6 +214,29 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
     s.ctx.close()
 
 
+def check_mul_relin(backend, n, k, seed_id=1, force_exact=False):
+    """General HMult on genuine and on uniformly random ciphertext pairs."""
+    s = Setup(backend, n, k, seed_id=seed_id, stream=3)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    slots, polys, er, gcts = s.encrypt_oracle(2)
+    rnd = gen.uniform_residues(s.rng, s.q, n, lead=(3, 2))
+    a = np.concatenate([gcts[:1], rnd[:2], rnd[2:3]])
+    b = np.concatenate([gcts[1:2], rnd[1:3], rnd[2:3]])          # last pair: a ciphertext with itself
+    if force_exact:
+        s.ctx.set_ambiguity_band(2 ** 26)
+    out = backend.host(s.ctx.ct_mul_relin(backend.dev(a), backend.dev(b)))
+    want = np.stack([fv.hmult(s.octx, a[i], b[i], s.evk) for i in range(len(a))])
+    assert np.array_equal(out, want), ("mul_relin", n, k)
+    assert np.array_equal(out[3], fv.square_relin(s.octx, a[3], s.evk))
+    m = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[0]), n, s.t)
+    assert np.array_equal(m, (slots[0].astype(np.uint64) * slots[1] % s.t).astype(np.uint32))
+    # in place on the first operand
+    buf = backend.dev(a)
+    s.ctx.ct_mul_relin(buf, backend.dev(b), out=buf)
+    assert np.array_equal(backend.host(buf), want)
+    s.ctx.close()
+
+
 def check_conv_layer_small(backend, seed_id=1):
     """A small convolution + square layer end to end: 1x6x6 image, 2 filters 3x3 stride 2 (+ one padded)."""
     n, k = 1024, 3

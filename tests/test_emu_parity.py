@@ -73,5 +73,11 @@ def test_square_relin_register_variants_of_standard_bases(backend, k, k_aux, big
     pc.check_square_relin(backend, 1024, k, n_random=1, n_genuine=0, t=t, force_exact=True)
 
 
+def test_general_hmult(backend):
+    pc.check_mul_relin(backend, 1024, 2)
+    pc.check_mul_relin(backend, 2048, 3, force_exact=True)
+    pc.check_mul_relin(backend, 1024, 8)
+
+
 def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
