@@ -230,12 +230,13 @@ int take_event(hcnn_ctx* c, hcnn_event_t* ev) {
 }
 
 // Launch on the context's stream; with profiling on, bracket the launch with two events.
+// `units` (default: the grid) is what the profile counts: the rows of an NTT launch whose grid is padded.
 template <class K, class Args>
-int run(hcnn_ctx* c, size_t grid, size_t lds_bytes, const Args& a) {
+int run(hcnn_ctx* c, size_t grid, size_t lds_bytes, const Args& a, size_t units = 0) {
   if (!c->profile || grid == 0) return launch<K>(c->stream, grid, lds_bytes, a);
   hcnn_ctx::Pending pd;
   pd.cls = KernelClass<K>::id;
-  pd.blocks = grid;
+  pd.blocks = units ? units : grid;
   int e;
   if ((e = take_event(c, &pd.start))) return e;
   if ((e = take_event(c, &pd.stop))) return e;
@@ -434,14 +435,17 @@ int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse, int io) {
   a.limb_cycle = r.cycle; a.limb_base = r.limb_base;
   a.in_group_rows = r.in_group_rows; a.in_row0 = r.in_row0;
   a.out_group_rows = r.out_group_rows; a.out_row0 = r.out_row0;
+  a.n_rows = (uint32_t)r.rows;
   const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;
   if (inverse) {
-    if (io == kNttLoadTensor) return run<NttInv<LOGN, LOGR, kNttLoadTensor>>(c, r.rows, lds, a);
-    if (io == kNttLoadTensorMul) return run<NttInv<LOGN, LOGR, kNttLoadTensorMul>>(c, r.rows, lds, a);
+    const size_t g3 = ntt_grouped_grid(r.rows, 3);
+    if (io == kNttLoadTensor) return run<NttInv<LOGN, LOGR, kNttLoadTensor>>(c, g3, lds, a, r.rows);
+    if (io == kNttLoadTensorMul) return run<NttInv<LOGN, LOGR, kNttLoadTensorMul>>(c, g3, lds, a, r.rows);
     if (io == kNttStoreAdd) return run<NttInv<LOGN, LOGR, kNttStoreAdd>>(c, r.rows, lds, a);
     return run<NttInv<LOGN, LOGR>>(c, r.rows, lds, a);
   }
-  if (io == kNttLoadDigit) return run<NttFwd<LOGN, LOGR, kNttLoadDigit>>(c, r.rows, lds, a);
+  if (io == kNttLoadDigit)
+    return run<NttFwd<LOGN, LOGR, kNttLoadDigit>>(c, ntt_grouped_grid(r.rows, r.cycle), lds, a, r.rows);
   return run<NttFwd<LOGN, LOGR>>(c, r.rows, lds, a);
 }
 

@@ -52,7 +52,24 @@ struct NttArgs {
   uint32_t limb_base;
   uint32_t in_group_rows, in_row0;
   uint32_t out_group_rows, out_row0;
+  uint32_t n_rows;          // rows of this launch (the grid may be padded, see ntt_logical_row)
 };
+
+// Workgroups are handed to the 8 accelerator dies round-robin by index, and each die has its own
+// L2.  The fused loads read one source row from several workgroups (a digit row feeds k transforms,
+// a c0^/c1^ row feeds two tensor components); this maps the workgroup index to a row so that the
+// `share` rows that read the same source run on the same die, next to each other in time.
+// Rows are numbered unit*share + within for the digit load (within = j) and the caller converts
+// for the tensor load.  Returns n_rows or more for the padding workgroups of the last round.
+constexpr uint32_t kNttXcds = 8;
+HCNN_HD uint32_t ntt_grouped_index(uint32_t bid, uint32_t share) {
+  const uint32_t xcd = bid % kNttXcds, local = bid / kNttXcds;
+  return ((local / share) * kNttXcds + xcd) * share + local % share;
+}
+inline size_t ntt_grouped_grid(size_t rows, size_t share) {
+  const size_t units = rows / share;
+  return (units + kNttXcds - 1) / kNttXcds * kNttXcds * share;
+}
 
 HCNN_HD size_t ntt_row(uint32_t r, uint32_t cycle, uint32_t group_rows, uint32_t row0) {
   return (size_t)(r / cycle) * group_rows + row0 + r % cycle;
@@ -97,6 +114,10 @@ struct NttFwd {
     constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
     constexpr bool kFirst = PH == 0, kLast = PH == kPhases - 1;
 
+    if constexpr (IO == kNttLoadDigit) {
+      bid = ntt_grouped_index(bid, a.limb_cycle);      // the k transforms of one digit row share a die
+      if (bid >= a.n_rows) return;
+    }
     const uint32_t limb = a.limb_base + bid % a.limb_cycle;
     const NttLimb L = ldc(a.limbs, limb);
     const uint32_t p = L.m.p, two_p = 2 * L.m.p;
@@ -182,6 +203,14 @@ struct NttInv {
     constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
     constexpr bool kFirst = PHI == 0, kLast = PHI == kPhases - 1;   // kLast <=> S0 == 0
 
+    if constexpr (IO == kNttLoadTensor || IO == kNttLoadTensorMul) {
+      // the three components of one (ciphertext, limb) pair read the same c0^ / c1^ rows: same die
+      const uint32_t LL = a.limb_cycle;
+      const uint32_t g = ntt_grouped_index(bid, 3);            // unit = ct*L + l, within = component
+      const uint32_t unit = g / 3, b = g % 3;
+      bid = ((unit / LL) * 3 + b) * LL + unit % LL;            // row (ct, b, l)
+      if (unit >= a.n_rows / 3) return;
+    }
     const uint32_t limb = a.limb_base + bid % a.limb_cycle;
     const NttLimb L = ldc(a.limbs, limb);
     const uint32_t p = L.m.p, two_p = 2 * L.m.p;
