@@ -181,7 +181,10 @@ enum {
                                    time (for tests) */
   HCNN_OPT_SQUARE_CHUNK = 1,    /* ciphertexts per internal batch of hcnn_ct_square_relin;
                                    0 = choose from the scratch budget */
-  HCNN_OPT_PROFILE = 2          /* non-zero: record a HIP event pair around every kernel launch */
+  HCNN_OPT_PROFILE = 2,         /* non-zero: record a HIP event pair around every kernel launch */
+  HCNN_OPT_RELIN_ORDER = 3      /* workgroup order of the evaluation-key inner product: 0 = chosen from
+                                   the key size (default), 1 = ciphertext-major, 2 = key-major (needs
+                                   n >= 8192).  Same results either way; for tests and tuning. */
 };
 int hcnn_set_option(hcnn_ctx* ctx, int which, uint64_t value);
 

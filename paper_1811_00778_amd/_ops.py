@@ -142,6 +142,9 @@ class OpsMixin:
     def profile(self):
         return self.raw.profile()
 
+    def set_relin_order(self, order):
+        self.raw.set_option(_capi.OPT_RELIN_ORDER, order)
+
     def set_square_chunk(self, chunk):
         self.raw.set_option(_capi.OPT_SQUARE_CHUNK, chunk)
 

@@ -191,14 +191,16 @@ struct ExtKernelT {
     const uint32_t v = bconv_round(S, a.band, exact, a.fallback_counter);
 #pragma unroll
     for (int i = 0; i < K; ++i) dst[(size_t)i * n] = x[i];
-#pragma unroll
-    for (int j = 0; j < KP; ++j) {
+    // rolled loop over the destination primes: row j of the transposed table is one contiguous scalar load
+#pragma unroll 1
+    for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
       const Mod dm = ldc(a.bc.dst_mod, j);
+      const uint32_t* bt = a.bc.BpT + (size_t)j * K;
       uint64_t acc = (uint64_t)v * ldc(a.bc.Vp, j);
 #pragma unroll
       for (int i = 0; i < K; ++i) {
-        acc += (uint64_t)z[i] * ldc(a.bc.Bp, i * KP + j);
-        if ((i & 7) == 7 && i + 1 < K) acc = reduce64(acc, dm);
+        acc += (uint64_t)z[i] * ldc(bt, i);
+        if ((i % 14) == 12 && i + 1 < K) acc = reduce64(acc, dm);
       }
       dst[(size_t)(K + j) * n] = reduce64(acc, dm);
     }
@@ -343,6 +345,8 @@ struct RelinMacArgs {
   uint32_t* acc;         // [n_ct][2][k][n]
   const Mod* mods;
   uint32_t k, n;
+  uint32_t n_ct;         // ciphertexts in this launch
+  uint32_t key_major;    // workgroup order, see the kernel
 };
 struct RelinMacKernel {
   static constexpr int kThreads = kEwThreads;
@@ -351,10 +355,24 @@ struct RelinMacKernel {
   template <int PH>
   HCNN_HD static void phase(const RelinMacArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
     const uint32_t per_row = a.n / (kThreads * kEwVec);
-    const size_t row = bid / per_row;                       // (ct, j)
-    const uint32_t c = ((bid % per_row) * kThreads + tid) * kEwVec;
-    const size_t ct = row / a.k;
-    const uint32_t j = (uint32_t)(row % a.k);
+    size_t ct;
+    uint32_t j, tile;
+    if (a.key_major) {
+      // (chosen by the host when the evaluation key outgrows an L2 in the plain order)
+      // die x takes the coefficient tiles x, x+8, ... ; for one (limb, tile) it sweeps the ciphertexts of
+      // the batch back to back, so the 2k evaluation-key tiles they all multiply with stay in that die's L2
+      const uint32_t xcd = bid % kXcds, local = bid / kXcds;
+      ct = local % a.n_ct;
+      const uint32_t rest = local / a.n_ct;
+      tile = (rest % (per_row / kXcds)) * kXcds + xcd;
+      j = rest / (per_row / kXcds);
+    } else {
+      const size_t row = bid / per_row;                     // (ct, j)
+      tile = bid % per_row;
+      ct = row / a.k;
+      j = (uint32_t)(row % a.k);
+    }
+    const uint32_t c = (tile * kThreads + tid) * kEwVec;
     const Mod m = ldc(a.mods, j);
     const size_t rn = a.n;
     uint64_t s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
@@ -364,7 +382,7 @@ struct RelinMacKernel {
       const U4 e1 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 1) * a.k + j) * rn + c);
       s0[0] += (uint64_t)d.x * e0.x; s0[1] += (uint64_t)d.y * e0.y; s0[2] += (uint64_t)d.z * e0.z; s0[3] += (uint64_t)d.w * e0.w;
       s1[0] += (uint64_t)d.x * e1.x; s1[1] += (uint64_t)d.y * e1.y; s1[2] += (uint64_t)d.z * e1.z; s1[3] += (uint64_t)d.w * e1.w;
-      if ((i & 15u) == 15u) {
+      if ((i % 15u) == 14u && i + 1 < a.k) {             // 15 products below 2^60 (+ a residue) fit 64 bits
         for (int q = 0; q < 4; ++q) { s0[q] = reduce64(s0[q], m); s1[q] = reduce64(s1[q], m); }
       }
     }

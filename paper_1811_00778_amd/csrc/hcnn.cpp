@@ -181,6 +181,7 @@ struct hcnn_ctx {
 
   uint32_t band = 128;
   uint64_t square_chunk = 0;
+  uint64_t relin_order = 0;   // 0 = by key size, 1 = ciphertext-major, 2 = key-major
   size_t max_lds = 0;
 
   // optional per-kernel timing (HCNN_OPT_PROFILE): an event pair around every launch
@@ -735,7 +736,11 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     if ((e = ntt_dense(c, y, dig, cc * k * k, k, false, kNttLoadDigit))) return e;
     // 7. inner product with the evaluation key
     RelinMacArgs ra;
-    ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
+    ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n; ra.n_ct = (uint32_t)cc;
+    // in the plain (ciphertext-major) order every die touches the key tiles of all limbs: 2*k*k*(tiles/8) * 4 KiB
+    ra.key_major = (bpr % kXcds == 0 && (size_t)2 * k * k * (bpr / kXcds) * 4096 > ((size_t)1 << 20)) ? 1u : 0u;
+    if (c->relin_order == 1) ra.key_major = 0;
+    if (c->relin_order == 2 && bpr % kXcds == 0) ra.key_major = 1;
     if ((e = run<RelinMacKernel>(c, cc * k * bpr, 0, ra))) return e;
     // 8. c'_b = y_b + sum_i evk[i][b] * digit_i : inverse transform with the addition on the way out
     if ((e = ntt_dense(c, acc, out + c0 * ct_words, cc * 2 * k, k, true, kNttStoreAdd, y))) return e;
@@ -915,6 +920,10 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
       return HCNN_OK;
     case HCNN_OPT_PROFILE:
       c->profile = value != 0;
+      return HCNN_OK;
+    case HCNN_OPT_RELIN_ORDER:
+      if (value > 2) return HCNN_ERR_ARG;
+      c->relin_order = value;
       return HCNN_OK;
   }
   return HCNN_ERR_ARG;

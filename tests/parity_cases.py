@@ -180,8 +180,10 @@ def slot_prime_above(n, lower):
 
 
 def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=None, force_exact=False,
-                       check_decrypt=True, t=65537, expect_k_aux=None):
+                       check_decrypt=True, t=65537, expect_k_aux=None, relin_order=None):
     s = Setup(backend, n, k, t=t, seed_id=seed_id)
+    if relin_order is not None:
+        s.ctx.set_relin_order(relin_order)
     if expect_k_aux is not None:
         assert len(s.p) == expect_k_aux
     s.ctx.set_relin_key(backend.dev(s.evk))

@@ -73,6 +73,13 @@ def test_square_relin_register_variants_of_standard_bases(backend, k, k_aux, big
     pc.check_square_relin(backend, 1024, k, n_random=1, n_genuine=0, t=t, force_exact=True)
 
 
+def test_square_relin_at_a_degree_with_die_aware_block_orders(backend):
+    # n = 8192: 8 coefficient tiles per row, the size from which the inner-product kernel orders its
+    # workgroups by accelerator die; three ciphertexts so that the ciphertext index is exercised too
+    pc.check_square_relin(backend, 8192, 2, n_random=3, n_genuine=0)
+    pc.check_square_relin(backend, 8192, 2, n_random=3, n_genuine=0, relin_order=2)    # key-major order forced
+
+
 def test_general_hmult(backend):
     pc.check_mul_relin(backend, 1024, 2)
     pc.check_mul_relin(backend, 2048, 3, force_exact=True)
