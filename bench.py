@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 ALU_PEAK_TOPS = 39.3           # 256 CU x 64 lanes x 2.4 GHz 32-bit integer VALU instructions / s
 
 
-def time_layer(cid, torch, binding, layers, gen, reps=3):
+def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
     """One conv layer + square activation at the shape of configuration `cid`: ms for the scalar MAC,
     ms for the squarings, compulsory-traffic bandwidth of the MAC.  Inputs are uniformly random residues
     generated on the device (timing does not depend on the values)."""
@@ -44,6 +44,7 @@ def time_layer(cid, torch, binding, layers, gen, reps=3):
     dev = ctx.to_device
     _, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
     ctx.set_relin_key(evk)
+    ctx.set_relin_order(relin_order)
     n_in = cv["c_in"] * cv["h"] * cv["w"]
     gtorch = torch.Generator(device=ctx.device)
     gtorch.manual_seed(gen.SEED_BASE + cid)
@@ -89,6 +90,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=3, help="squarings the oracle computes for cpu_baseline")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
     ap.add_argument("--no-layers", action="store_true", help="skip the conv-layer timings (configs 3 and 4)")
+    ap.add_argument("--relin-order", type=int, default=0, help="HCNN_OPT_RELIN_ORDER (tuning experiments)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain device copy of 256 MiB (a reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -111,6 +113,7 @@ def main():
     kr = gen.key_randomness(rng, q, n)
     _, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
     ctx.set_relin_key(evk)
+    ctx.set_relin_order(args.relin_order)
     cts_host = gen.uniform_residues(rng, q, n, lead=(n_ct, 2))
     cts = dev(cts_host)
     F, wb = 5, 15
@@ -213,7 +216,7 @@ def main():
     layers_out = {}
     if not args.no_layers:
         for cid in (3, 4, 5):
-            layers_out[gen.CONFIGS[cid]["name"]] = time_layer(cid, torch, binding, layers, gen)
+            layers_out[gen.CONFIGS[cid]["name"]] = time_layer(cid, torch, binding, layers, gen, relin_order=args.relin_order)
 
     # ---- CPU oracle on a bounded sample of the same squarings (also a parity check)
     cpu = None
