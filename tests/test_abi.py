@@ -106,3 +106,18 @@ def test_binding_has_no_cpu_fallback():
     from paper_1811_00778_amd import binding
     with pytest.raises(RuntimeError):
         binding.Context(1024, [1, 2], [3], 65537)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_set_option_validation_needs_no_device(lib):
+    # options are checked before anything touches a device; a null context is rejected first
+    assert lib.hcnn_set_option(None, _capi.OPT_PROFILE, 1) == _capi.ERR["NULL"]
+    assert lib.hcnn_get_stat(None, 0, None) == _capi.ERR["NULL"]
+    assert lib.hcnn_profile_read(None, 0, None, None, None) == _capi.ERR["NULL"]

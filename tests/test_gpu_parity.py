@@ -104,6 +104,34 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_options_and_profile(backend):
+    """Option validation, the per-kernel profile and the counters on a live context."""
+    from paper_1811_00778_amd import _capi
+    s = pc.Setup(backend, 1024, 2)
+    ctx = s.ctx
+    with pytest.raises(_capi.HcnnError):
+        ctx.set_ambiguity_band(3)                      # below the error bound of the estimate
+    with pytest.raises(_capi.HcnnError):
+        ctx.set_ambiguity_band(2 ** 27)
+    with pytest.raises(_capi.HcnnError):
+        ctx.set_relin_order(7)
+    with pytest.raises(_capi.HcnnError):
+        ctx.ct_square_relin(backend.dev(np.zeros((1, 2, 2, 1024), dtype=np.uint32)))     # no key yet
+    ctx.set_relin_key(backend.dev(s.evk))
+    ctx.set_profile(True)
+    x = backend.dev(gen.uniform_residues(s.rng, s.q, 1024, lead=(3, 2)))
+    ctx.ntt_fwd(x); ctx.ntt_inv(x)
+    ctx.ct_square_relin(x)
+    prof = ctx.profile()
+    assert prof["ntt_fwd"][0] == 3 and prof["ntt_fwd"][1] == 3 * 2 * 2 + 3 * 2 * 5 + 3 * 4   # rows: plain, ext, digits
+    assert prof["ntt_inv"][0] == 3 and prof["scale"][0] == 1 and prof["base_ext"][0] == 1
+    assert all(v[2] > 0 for k, v in prof.items() if v[0])
+    ctx.reset_stats()
+    assert all(v[0] == 0 for v in ctx.profile().values())
+    assert ctx.scratch_bytes() > 0
+    ctx.close()
+
+
 def test_empty_batches_are_noops(backend):
     s = pc.Setup(backend, 1024, 2)
     ctx = s.ctx
