@@ -487,7 +487,7 @@ struct MacKernel {
   static constexpr int kPhases = 2;
   struct Regs {};
   static size_t padded_terms(size_t T) { return (T + kMacBatch - 1) / kMacBatch * kMacBatch; }
-  static size_t lds_bytes(size_t F, size_t T) { return (1 + F) * padded_terms(T) * 4; }
+  static size_t lds_bytes(size_t F, size_t T) { return ((1 + F) * padded_terms(T) + 2 * kMacBatch) * 4; }
   static size_t grid(size_t tiles, size_t G) { return kXcds * ((tiles + kXcds - 1) / kXcds) * G; }
   template <int PH>
   HCNN_HD static void phase(const MacArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
@@ -503,12 +503,16 @@ struct MacKernel {
     const uint32_t g = local % a.G;
     if (tile >= tiles) return;                                        // padding blocks (whole block)
     const uint32_t Tpad = (a.T + kMacBatch - 1) / kMacBatch * kMacBatch;
-    uint32_t* l_idx = lds;                                            // [Tpad]
-    int32_t* l_w = reinterpret_cast<int32_t*>(lds + Tpad);            // [F][Tpad]
+    uint32_t* l_idx = lds;                                            // [Tpad + 2*kMacBatch]
+    int32_t* l_w = reinterpret_cast<int32_t*>(lds + Tpad + 2 * kMacBatch);   // [F][Tpad]
     if constexpr (PH == 0) {
       const uint32_t* idx = a.idx + (size_t)g * a.T;
       const int32_t* w = a.w + (size_t)g * a.F * a.T;
-      for (uint32_t tau = tid; tau < Tpad; tau += kThreads) {
+      for (uint32_t tau = tid; tau < Tpad + 2 * kMacBatch; tau += kThreads) {
+        if (tau >= Tpad) {                 // read-ahead slots of the last batches
+          l_idx[tau] = 0;
+          continue;
+        }
         const bool pad = tau >= a.T;
         uint32_t src = pad ? 0u : idx[tau];
         const bool bad_src = src >= a.n_in;
@@ -563,17 +567,19 @@ struct MacKernel {
           for (int q = 0; q < 4; ++q) s[f][q] = bias + reduce64(s[f][q], m);
       };
       // two register buffers used alternately: the loads of the next batch are in flight while the
-      // current one is consumed
+      // current one is consumed.  Every fetch is unconditional (the gather row is followed by 2*kMacBatch
+      // entries that point at input 0) so that the number of loads in flight is the same on every path
+      // and the compiler can wait for exactly the older batch.
       U4 buf_a[kMacBatch], buf_b[kMacBatch];
       fetch(buf_a, 0);
       uint32_t since = 0;
       for (uint32_t tau = 0; tau < Tpad; tau += 2 * kMacBatch) {
-        if (tau + kMacBatch < Tpad) fetch(buf_b, tau + kMacBatch);
+        fetch(buf_b, tau + kMacBatch);
         if (since >= a.chunk) { since = 0; refold(); }
         since += kMacBatch;
         consume(buf_a, tau);
+        fetch(buf_a, tau + 2 * kMacBatch);
         if (tau + kMacBatch < Tpad) {
-          if (tau + 2 * kMacBatch < Tpad) fetch(buf_a, tau + 2 * kMacBatch);
           if (since >= a.chunk) { since = 0; refold(); }
           since += kMacBatch;
           consume(buf_b, tau + kMacBatch);

@@ -494,7 +494,7 @@ int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
   const size_t lds = MacKernel<FT>::lds_bytes(a.F, a.T);
   const size_t tiles = grid / a.G;
   const bool offsets_fit = (uint64_t)a.n_in * 2 * a.k * a.n <= 0xffffffffull;   // word offsets kept in 32 bits
-  if (lds <= 64 * 1024 && lds <= c->max_lds && a.chunk >= kMacBatch && offsets_fit) {
+  if (lds <= 64 * 1024 && lds <= c->max_lds && a.chunk >= kMacBatch && a.T >= kMacBatch && offsets_fit) {
     MacArgs b = a;
     b.chunk = a.chunk / kMacBatch * kMacBatch;      // the staged kernel reduces at batch boundaries
     return run<MacKernel<FT>>(c, MacKernel<FT>::grid(tiles, a.G), lds, b);
@@ -668,7 +668,7 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
   // partial sums stay below 2^62 in magnitude: chunk * w_abs_max * 2^30 + 2^30 <= 2^62
   const uint64_t wm = w_abs_max > 0 ? (uint64_t)w_abs_max : 1;
   uint64_t chunk = ((1ull << 32) - 1) / wm;
-  if (chunk > T) chunk = T;
+  if (chunk > (1u << 30)) chunk = 1u << 30;          // a row shorter than the chunk is never folded midway
   a.chunk = (uint32_t)chunk;
   a.bad_counter = c->d_counters + 1;
   return mac_dispatch(c, G * tiles, a);
