@@ -580,7 +580,7 @@ int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, u
   if (k_aux) c->p.assign(p, p + k_aux);
   c->stream = (hcnn_stream_t)hip_stream;
   c->max_lds = max_lds_bytes();
-  if (c->max_lds < (size_t)n * 4) {
+  if (c->max_lds < (size_t)(n + n / 32) * 4) {
     delete c;
     return HCNN_ERR_NODEVICE;
   }

@@ -75,15 +75,14 @@ HCNN_HD size_t ntt_row(uint32_t r, uint32_t cycle, uint32_t group_rows, uint32_t
   return (size_t)(r / cycle) * group_rows + row0 + r % cycle;
 }
 
-// LDS index swizzle: spreads power-of-two strides over the 32 banks.  It is linear over XOR,
-// swz(a ^ b) = swz(a) ^ swz(b), and leaves bits >= 5 alone; the element e of a network sits at
-// base | (e << LOG_TLAST) with those bits of base clear, so its LDS word is
-// (swz(base) ^ low) + high with compile-time low = swz(field) & 1023 and high = field & ~1023.
-HCNN_HD constexpr uint32_t lds_swz(uint32_t i) { return i ^ ((i >> 5) & 31u); }
+// LDS layout: one unused word after every 32, which spreads the power-of-two strides of the passes
+// over the 32 banks.  The map a -> a + a/32 is additive over operands with disjoint bit fields (no
+// carries), and the element e of a network sits at base | (e << LOG_TLAST) with those bits of base
+// clear: its LDS word is pad(base) + pad(e << LOG_TLAST), a register plus a compile-time offset.
+HCNN_HD constexpr uint32_t lds_swz(uint32_t i) { return i + (i >> 5); }
 template <int LOG_TLAST>
 HCNN_HD constexpr uint32_t lds_elem(uint32_t sbase, int e) {
-  const uint32_t field = (uint32_t)e << LOG_TLAST;
-  return (sbase ^ (lds_swz(field) & 1023u)) + (field & ~1023u);
+  return sbase + lds_swz((uint32_t)e << LOG_TLAST);
 }
 
 template <int LOGN, int LOGR>
@@ -92,7 +91,7 @@ struct NttGeom {
   static constexpr int R = 1 << LOGR;
   static constexpr int kThreads = N / R;
   static constexpr int kPhases = (LOGN + LOGR - 1) / LOGR;
-  static constexpr size_t kLdsBytes = (size_t)N * 4;
+  static constexpr size_t kLdsBytes = (size_t)(N + N / 32) * 4;
   // forward pass PH covers stages [s0(PH), s0(PH)+ns(PH))
   static constexpr int s0(int ph) { return ph * LOGR; }
   static constexpr int ns(int ph) { return ph < kPhases - 1 ? LOGR : LOGN - LOGR * (kPhases - 1); }
