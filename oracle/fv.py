@@ -398,3 +398,20 @@ def slot_encode(values, n: int, t: int):
 
 def slot_decode(poly, n: int, t: int):
     return ntt_forward(np.asarray(poly, dtype=np.uint32) % t, t, natural=True)
+
+
+def slot_eval(polys, n: int, t: int, slots):
+    """Values of the chosen slots only: polys [m][n] in R_t -> [m][len(slots)], slot j being the value
+    of the polynomial at psi_t^(2j+1) (the evaluation view of the plaintext CRT map, Sec. 2.1.1).
+    Written as the evaluation itself, for use where only a few slots of many polynomials are needed."""
+    polys = np.asarray(polys, dtype=np.int64) % t
+    assert polys.ndim == 2 and polys.shape[1] == n and t < (1 << 24)
+    psi = root_of_unity(n, t)
+    out = np.zeros((polys.shape[0], len(slots)), dtype=np.int64)
+    for col, j in enumerate(slots):
+        x = pow(psi, 2 * int(j) + 1, t)
+        powers = np.ones(n, dtype=np.int64)
+        for i in range(1, n):
+            powers[i] = powers[i - 1] * x % t
+        out[:, col] = (polys @ powers) % t          # n terms below 2^48 each: exact in int64
+    return out

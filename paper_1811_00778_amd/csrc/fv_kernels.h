@@ -520,7 +520,7 @@ struct MacKernel {
           src = 0;
           if (tile == 0) atomic_inc64(a.bad_counter);
         }
-        l_idx[tau] = src * ct_words32;       // word offset of the input (the host checked that it fits)
+        l_idx[tau] = src * (ct_words32 / 4);   // offset of the input in 16-byte units (the host checked that it fits)
 #pragma unroll
         for (int f = 0; f < FT; ++f) {
           int32_t wf = pad ? 0 : w[(size_t)f * a.T + tau];
@@ -535,7 +535,7 @@ struct MacKernel {
       const uint32_t pos = (tile * kThreads + tid) * kEwVec;          // word offset inside a ciphertext
       const uint32_t row = tile / (a.n / (kThreads * kEwVec));        // (poly, limb) row; uniform in the block
       const Mod m = ldc(a.mods, row % a.k);
-      const uint32_t* in = a.in + pos;
+      const U4* in = reinterpret_cast<const U4*>(a.in + pos);
       // accumulators carry the bias p*2^33 (a multiple of p above 2^62), so they stay positive while
       // the signed partial sums stay inside (-2^62, 2^62) and one unsigned reduction folds them
       const uint64_t bias = (uint64_t)m.p << 33;
@@ -545,7 +545,7 @@ struct MacKernel {
       auto fetch = [&](U4 (&buf)[kMacBatch], uint32_t t) {
 #pragma unroll
         for (uint32_t b = 0; b < kMacBatch; ++b)
-          buf[b] = *reinterpret_cast<const U4*>(in + (size_t)l_idx[t + b]);     // l_idx holds word offsets
+          buf[b] = in[(size_t)l_idx[t + b]];
       };
       auto consume = [&](const U4 (&buf)[kMacBatch], uint32_t t) {
 #pragma unroll

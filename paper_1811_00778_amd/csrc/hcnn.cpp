@@ -475,7 +475,7 @@ int ext_dispatch(hcnn_ctx* c, size_t grid, const ExtArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_EXT_CASE(K, KP) \
   if (k == K && kp == KP) return run<ExtKernelT<K, KP>>(c, grid, ExtKernelT<K, KP>::lds_bytes(), a);
-  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
+  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(11, 12) HCNN_EXT_CASE(12, 14) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
 #undef HCNN_EXT_CASE
   return run<ExtKernel>(c, grid, ExtKernel::lds_bytes(k), a);
 }
@@ -484,7 +484,7 @@ int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_SCALE_CASE(K, KP) \
   if (k == K && kp == KP) return run<ScaleKernelR<K, KP>>(c, grid, ScaleKernelR<K, KP>::lds_bytes(), a);
-  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
+  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(11, 12) HCNN_SCALE_CASE(12, 14) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
 #undef HCNN_SCALE_CASE
   return run<ScaleKernel>(c, grid, ScaleKernel::lds_bytes(k, kp), a);
 }
@@ -493,7 +493,7 @@ template <int FT>
 int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
   const size_t lds = MacKernel<FT>::lds_bytes(a.F, a.T);
   const size_t tiles = grid / a.G;
-  const bool offsets_fit = (uint64_t)a.n_in * 2 * a.k * a.n <= 0xffffffffull;   // word offsets kept in 32 bits
+  const bool offsets_fit = (uint64_t)a.n_in * 2 * a.k * a.n / 4 <= 0xffffffffull;   // 16-byte offsets kept in 32 bits
   if (lds <= 64 * 1024 && lds <= c->max_lds && a.chunk >= kMacBatch && a.T >= kMacBatch && offsets_fit) {
     MacArgs b = a;
     b.chunk = a.chunk / kMacBatch * kMacBatch;      // the staged kernel reduces at batch boundaries

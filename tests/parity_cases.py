@@ -266,3 +266,48 @@ def check_conv_layer_small(backend, seed_id=1):
                 got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], sq[o]), n, s.t)
                 assert np.array_equal(got.astype(np.int64), want), ("conv+square", f, j, kk)
     s.ctx.close()
+
+
+def check_small_network(backend, seed_id=1):
+    """A CIFAR-shaped miniature (padded 3x3 convolution, square, 2x2 sum pooling, fully connected) run through
+    the network runner; every layer's ciphertexts must equal the oracle's, residue by residue, and the result
+    must decrypt to the plain network on the slot values."""
+    from oracle import plain_net
+    from paper_1811_00778_amd import network
+    n, k = 1024, 4
+    spec = (("conv", 3, 3, 3, 1, 1), ("square",), ("pool", 2), ("fc", 2))
+    in_shape = (2, 4, 4)
+    s = Setup(backend, n, k, seed_id=seed_id, stream=9)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    n_in = in_shape[0] * in_shape[1] * in_shape[2]
+    slots, polys, er, cts = s.encrypt_oracle(n_in, high=16)
+    weights = [None if shp is None else gen.int_weights(s.rng, shp, 3)
+               for shp in network.weight_shapes(spec, in_shape)]
+    plan = network.Plan(spec, in_shape, weights, backend.dev)
+    out, kept = plan.run(s.ctx, backend.dev(cts), keep=True)
+    # the oracle, layer by layer, on its own previous output
+    cur = cts
+    prev = in_shape
+    for li, (layer, shp) in enumerate(zip(spec, network.shapes(spec, in_shape))):
+        if layer[0] == "square":
+            cur = np.stack([fv.square_relin(s.octx, cur[i], s.evk) for i in range(cur.shape[0])])
+        else:
+            if layer[0] == "conv":
+                idx, valid, _ = layers.conv_index_table(prev[0], prev[1], prev[2], layer[2], layer[3], layer[4], layer[5])
+                wt = layers.conv_weight_table(weights[li], idx.shape[0], valid)
+            elif layer[0] == "pool":
+                idx, wt, _ = layers.pool_index_table(prev[0], prev[1], prev[2], layer[1])
+            else:
+                idx = layers.fc_index_table(prev[0] * prev[1] * prev[2])
+                wt = layers.fc_weight_table(weights[li])
+            G, F, T = wt.shape
+            cur = np.stack([fv.scalar_mac(s.octx, cur, idx[g], wt[g, f]) for f in range(F) for g in range(G)])
+        assert cur.shape[0] == shp[0] * shp[1] * shp[2]
+        assert np.array_equal(backend.host(kept[li]), cur), ("network layer", li, layer)
+        prev = shp
+    want = plain_net.evaluate(spec, weights, slots.astype(np.int64).reshape(in_shape + (n,)), s.t).reshape(2, n)
+    final = backend.host(out)
+    for o in range(2):
+        got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], final[o]), n, s.t).astype(np.int64)
+        assert np.array_equal(got, want[o]), ("network output", o)
+    s.ctx.close()

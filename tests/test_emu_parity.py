@@ -89,3 +89,7 @@ def test_general_hmult(backend):
 
 def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
+
+
+def test_small_network_layer_by_layer(backend):
+    pc.check_small_network(backend)

@@ -1,6 +1,12 @@
-"""The whole MNIST-shaped HCNN (conv 5x5x5 stride 2 -> square -> conv 50x5x5x5 stride 2 -> square ->
-fully connected 800 -> 10) on one GPU, synthetic integer weights, 8192 images in the slots.
-The ten decrypted outputs must equal the network evaluated in plain integers mod t on the slot values."""
+"""Whole HCNN-shaped networks on one GPU with synthetic integer weights, one image per plaintext slot.
+
+MNIST shape (Table 1): conv 5x5x5 stride 2 -> square -> conv 50x5x5x5 stride 2 -> square -> fully connected 800 -> 10.
+CIFAR-10 shape (Table 2) at the paper's full widths: three blocks of padded 3x3 convolution (32 / 64 / 128 filters),
+square and 2x2 average pooling, then fully connected 2048 -> 256 -> 10; n = 2^14 and a 360-bit q as in Table 5.
+
+The decrypted outputs must equal the network evaluated in plain integers mod t on the slot values
+(every slot for MNIST, sampled slots for CIFAR-10).  Residue-level parity of each operation with the oracle is the
+business of test_gpu_parity.py; here the oracle decrypts and supplies the plain network."""
 import sys
 import time
 
@@ -8,7 +14,7 @@ import numpy as np
 import pytest
 
 import parity_cases as pc
-from oracle import fv
+from oracle import fv, plain_net
 from workloads import generators as gen
 
 pytestmark = pytest.mark.gpu
@@ -19,22 +25,16 @@ def say(msg):
     sys.stdout.flush()
 
 
-def _mac_layer(ctx, dev, cts, idx, w, bound):
-    """Scalar MAC with any number of filters (the entry point takes at most 16 per call)."""
-    import torch
-    G, F, T = w.shape
-    out = torch.empty((F, G) + tuple(cts.shape[1:]), dtype=torch.int32, device=cts.device)
-    didx = dev(idx)
-    for f0 in range(0, F, 16):
-        f1 = min(F, f0 + 16)
-        ctx.ct_scalar_mac(cts, didx, dev(np.ascontiguousarray(w[:, f0:f1, :])), bound, out=out[f0:f1])
-    return out.reshape((F * G,) + tuple(cts.shape[1:]))
+def _weights(rng, spec, in_shape, bound):
+    from paper_1811_00778_amd import network
+    return [None if shp is None else gen.int_weights(rng, shp, bound)
+            for shp in network.weight_shapes(spec, in_shape)]
 
 
 def test_mnist_network_end_to_end():
     import torch
     from test_gpu_parity import GpuBackend
-    from paper_1811_00778_amd import layers
+    from paper_1811_00778_amd import network
     backend = GpuBackend()
     n, k, t = 8192, 8, 65537
     s = pc.Setup(backend, n, k, seed_id=3, stream=11)
@@ -45,48 +45,72 @@ def test_mnist_network_end_to_end():
     polys = rng.integers(0, t, size=(784, n), dtype=np.int64).astype(np.uint32)
     er = gen.encryption_randomness(rng, n, 784)
     cts = ctx.encrypt(dev(s.pk), dev(polys), dev(er["u"]), dev(er["e1"]), dev(er["e2"]))
-    w1 = gen.int_weights(rng, (5, 1, 5, 5), 15)
-    w2 = gen.int_weights(rng, (50, 5, 5, 5), 15)
-    w3 = gen.int_weights(rng, (10, 800), 15)
-    idx1, _, (h1, v1) = layers.conv_index_table(1, 28, 28, 5, 5, 2)
-    idx2, _, (h2, v2) = layers.conv_index_table(5, h1, v1, 5, 5, 2)
-    assert (h1, v1, h2, v2) == (12, 12, 4, 4)
+    weights = _weights(rng, network.MNIST_HCNN, network.MNIST_INPUT, 15)
+    plan = network.Plan(network.MNIST_HCNN, network.MNIST_INPUT, weights, dev)
+    plan.run(ctx, cts)                                   # warm-up (allocator, first launches)
     torch.cuda.synchronize()
     t0 = time.time()
-    a1 = _mac_layer(ctx, dev, cts, idx1, layers.conv_weight_table(w1, idx1.shape[0]), 15)          # 720
-    a2 = ctx.ct_square_relin(a1)
-    a3 = _mac_layer(ctx, dev, a2, idx2, layers.conv_weight_table(w2, idx2.shape[0]), 15)           # 800
-    a4 = ctx.ct_square_relin(a3)
-    a5 = _mac_layer(ctx, dev, a4, layers.fc_index_table(800), layers.fc_weight_table(w3), 15)      # 10
+    a5 = plan.run(ctx, cts)
     torch.cuda.synchronize()
-    say("encrypted network (46000-odd plaintext multiplications, 1520 squarings): %.1f ms on the GPU"
-        % ((time.time() - t0) * 1e3))
-    assert a1.shape[0] == 720 and a3.shape[0] == 800 and a5.shape[0] == 10
+    say("encrypted network (1520 squarings): %.1f ms on the GPU" % ((time.time() - t0) * 1e3))
+    assert a5.shape[0] == 10
     out = backend.host(a5)
 
     say("plain evaluation mod t on the slot values")
     slots = np.stack([fv.slot_decode(polys[i], n, t) for i in range(784)]).astype(np.int64)   # [784][n]
-    x = slots.reshape(1, 28, 28, n)
-
-    def conv(x, w, stride):
-        F, C, fh, fw = w.shape
-        ho, wo = (x.shape[1] - fh) // stride + 1, (x.shape[2] - fw) // stride + 1
-        y = np.zeros((F, ho, wo, n), dtype=np.int64)
-        for f in range(F):
-            for c in range(C):
-                for dy in range(fh):
-                    for dx in range(fw):
-                        y[f] += int(w[f, c, dy, dx]) * x[c, dy:dy + stride * ho:stride, dx:dx + stride * wo:stride]
-        return y % t
-
-    y = conv(x, w1, 2)
-    y = y * y % t
-    y = conv(y, w2, 2)
-    y = y * y % t
-    flat = y.reshape(800, n)
-    want = (w3.astype(np.int64) @ flat) % t                                                   # [10][n]
+    want = plain_net.evaluate(network.MNIST_HCNN, weights, slots.reshape(1, 28, 28, n), t).reshape(10, n)
     say("oracle decryption of the ten outputs")
     for o in range(10):
         got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[o]), n, t).astype(np.int64)
         assert np.array_equal(got, want[o]), ("network output", o)
+    ctx.close()
+
+
+def test_cifar10_network_full_width_end_to_end():
+    import torch
+    from test_gpu_parity import GpuBackend
+    from paper_1811_00778_amd import network
+    backend = GpuBackend()
+    n, k, t = 16384, 12, 65537
+    free, _total = torch.cuda.mem_get_info()
+    if free < 130 * 2 ** 30:
+        pytest.skip("needs about 110 GiB of device memory")
+    s = pc.Setup(backend, n, k, seed_id=4, stream=12, with_keys=False)
+    ctx, dev = s.ctx, backend.dev
+    rng = s.rng
+    say("keys on the GPU (key generation is checked against the oracle elsewhere)")
+    kr = gen.key_randomness(rng, s.q, n)
+    pk, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
+    ctx.set_relin_key(evk)
+    n_in = 3 * 32 * 32
+    say("plaintexts and GPU encryption of %d ciphertexts" % n_in)
+    polys = rng.integers(0, t, size=(n_in, n), dtype=np.int64).astype(np.uint32)
+    cts = torch.empty((n_in, 2, k, n), dtype=torch.int32, device="cuda")
+    for i0 in range(0, n_in, 512):
+        er = gen.encryption_randomness(rng, n, 512)
+        cts[i0:i0 + 512] = ctx.encrypt(pk, dev(polys[i0:i0 + 512]), dev(er["u"]), dev(er["e1"]), dev(er["e2"]))
+    del er
+    weights = _weights(rng, network.CIFAR10_HCNN, network.CIFAR10_INPUT, 7)
+    say("gather tables")
+    plan = network.Plan(network.CIFAR10_HCNN, network.CIFAR10_INPUT, weights, dev)
+    torch.cuda.synchronize()
+    say("encrypted network: 57344 squarings, about 10.8 million ciphertext-by-scalar products")
+    t0 = time.time()
+    out = plan.run(ctx, cts)
+    torch.cuda.synchronize()
+    say("encrypted network: %.2f s on the GPU (cold), exact-rounding fall-backs %d" % (time.time() - t0, ctx.exact_fallbacks()))
+    assert out.shape[0] == 10
+    host_out = backend.host(out)
+    del out
+    torch.cuda.empty_cache()
+
+    picks = [0, 1, 4097, 9999, n - 1]
+    say("plain evaluation mod t on %d sampled slots" % len(picks))
+    x = fv.slot_eval(polys, n, t, picks).reshape(3, 32, 32, len(picks))
+    want = plain_net.evaluate(network.CIFAR10_HCNN, weights, x, t).reshape(10, len(picks))
+    say("oracle decryption of the ten outputs")
+    for o in range(10):
+        m = fv.decrypt(s.octx, kr["s"], host_out[o])
+        got = fv.slot_eval(m[None, :], n, t, picks)[0]
+        assert np.array_equal(got, want[o]), ("network output", o, got, want[o])
     ctx.close()

@@ -104,6 +104,11 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_small_network_layer_by_layer(backend):
+    say("miniature network (padded conv, square, pooling, fully connected), every layer against the oracle")
+    pc.check_small_network(backend)
+
+
 def test_options_and_profile(backend):
     """Option validation, the per-kernel profile and the counters on a live context."""
     from paper_1811_00778_amd import _capi

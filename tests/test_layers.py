@@ -90,3 +90,30 @@ def test_padded_stride1_conv_keeps_the_feature_map_size():
     idx, valid, (ho, wo) = layers.conv_index_table(3, 32, 32, 3, 3, 1, pad=1)
     assert (ho, wo) == (32, 32) and idx.shape == (1024, 27)
     assert valid.sum() == 27 * 1024 - 3 * (4 * 5 + 4 * 30 * 3)        # corner and edge placements lose terms
+
+
+def test_network_shapes_match_paper_tables():
+    """Layer sizes and squaring counts of both architectures against the paper's tables."""
+    from paper_1811_00778_amd import network
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "cifar_layer_sizes.txt")) if l[0] not in "#\n"]
+    table = [r for r in rows if r[0].isdigit()]
+    extra = {r[0]: int(r[1]) for r in rows if not r[0].isdigit()}
+    shp = network.shapes(network.CIFAR10_HCNN, network.CIFAR10_INPUT)
+    assert len(shp) == len(table) == len(network.CIFAR10_HCNN)
+    hmult = 0
+    for layer, got, row in zip(network.CIFAR10_HCNN, shp, table):
+        assert layer[0] == row[1]
+        assert got == (int(row[2]), int(row[3]), int(row[4]))
+        assert got[0] * got[1] * got[2] == int(row[5])
+        hmult += int(row[6])
+    assert hmult == extra["total_hmult"]
+    assert network.op_counts(network.CIFAR10_HCNN, network.CIFAR10_INPUT)[1] == extra["total_hmult"]
+    c, h, w = network.CIFAR10_INPUT
+    assert c * h * w == extra["input_neurons"]
+    g = _golden("mnist_layer_counts.txt")
+    mshp = network.shapes(network.MNIST_HCNN, network.MNIST_INPUT)
+    assert mshp[0] == (5, 12, 12) and mshp[2] == (50, 4, 4) and mshp[4] == (10, 1, 1)
+    assert network.op_counts(network.MNIST_HCNN, network.MNIST_INPUT)[1] == int(g["total_hsquare"][0])
+    ws = network.weight_shapes(network.CIFAR10_HCNN, network.CIFAR10_INPUT)
+    assert ws[0] == (32, 3, 3, 3) and ws[3] == (64, 32, 3, 3) and ws[6] == (128, 64, 3, 3)
+    assert ws[9] == (256, 2048) and ws[10] == (10, 256) and ws[1] is None and ws[2] is None
