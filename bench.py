@@ -81,6 +81,47 @@ def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
                 squarings=int(flat.shape[0]), squarings_per_s=round(flat.shape[0] / (sq * 1e-3), 1))
 
 
+def time_network(name, spec, in_shape, n, k, w_bound, torch, binding, network, gen, reps=2):
+    """A whole HCNN-shaped network (architecture tables of Sec. 3.2) at the ring degree and modulus size of the
+    paper's parameter table, one plaintext channel (t = 65537), random ciphertexts and random integer weights
+    resident in HBM: seconds per evaluation, excluding encryption and table upload."""
+    t = 65537
+    free, _ = torch.cuda.mem_get_info()
+    shp = [in_shape] + network.shapes(spec, in_shape)
+    ct_bytes = 2 * k * n * 4
+    need = 2.5 * max(a[0] * a[1] * a[2] for a in shp) * ct_bytes + 8 * 2 ** 30
+    if free < need:
+        return dict(skipped="needs about %.0f GiB of device memory" % (need / 2 ** 30))
+    q, p = binding.choose_moduli(n, k, t)
+    ctx = binding.Context(n, q, p, t, device="cuda:0")
+    rng = gen.rng_for(2, 7)
+    kr = gen.key_randomness(rng, q, n)
+    dev = ctx.to_device
+    _, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
+    ctx.set_relin_key(evk)
+    weights = [None if ws is None else gen.int_weights(rng, ws, w_bound) for ws in network.weight_shapes(spec, in_shape)]
+    plan = network.Plan(spec, in_shape, weights, dev)
+    gtorch = torch.Generator(device=ctx.device)
+    gtorch.manual_seed(gen.SEED_BASE + 77)
+    n_in = in_shape[0] * in_shape[1] * in_shape[2]
+    cts = torch.randint(0, 1 << 29, (n_in, 2, k, n), dtype=torch.int32, device=ctx.device, generator=gtorch)
+    times = []
+    for r in range(reps + 1):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = plan.run(ctx, cts)
+        torch.cuda.synchronize()
+        if r:                                      # the first evaluation allocates scratch and feature maps
+            times.append(time.perf_counter() - t0)
+        del out
+    ctx.close()
+    torch.cuda.empty_cache()
+    n_mul, n_sq = network.op_counts(spec, in_shape)
+    sec = sorted(times)[len(times) // 2]
+    return dict(n=n, k=k, k_aux=len(p), inputs=n_in, squarings=n_sq, scalar_products_dense=n_mul,
+                seconds=round(sec, 4), squarings_per_s=round(n_sq / sec, 1))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +131,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=3, help="squarings the oracle computes for cpu_baseline")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
     ap.add_argument("--no-layers", action="store_true", help="skip the conv-layer timings (configs 3 and 4)")
+    ap.add_argument("--no-networks", action="store_true", help="skip the whole-network timings")
     ap.add_argument("--relin-order", type=int, default=0, help="HCNN_OPT_RELIN_ORDER (tuning experiments)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain device copy of 256 MiB (a reference dispatch for HBM byte counters)")
@@ -218,6 +260,16 @@ def main():
         for cid in (3, 4, 5):
             layers_out[gen.CONFIGS[cid]["name"]] = time_layer(cid, torch, binding, layers, gen, relin_order=args.relin_order)
 
+    # ---- whole networks at the paper's sizes (Table 5: n = 2^13 / 330-bit q for MNIST, n = 2^14 / 360-bit q for
+    #      CIFAR-10), one plaintext channel each
+    networks_out = {}
+    if not args.no_networks:
+        from paper_1811_00778_amd import network
+        networks_out["mnist-hcnn"] = time_network("mnist", network.MNIST_HCNN, network.MNIST_INPUT, 8192, 11, 15,
+                                                  torch, binding, network, gen)
+        networks_out["cifar10-hcnn"] = time_network("cifar10", network.CIFAR10_HCNN, network.CIFAR10_INPUT, 16384, 12, 7,
+                                                    torch, binding, network, gen)
+
     # ---- CPU oracle on a bounded sample of the same squarings (also a parity check)
     cpu = None
     if not args.no_cpu_baseline:
@@ -256,6 +308,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "conv_layers": layers_out,
+        "networks": networks_out,
         "kernels": kernels,
         "profiled_pass_ms_per_step": None if elapsed_prof is None else round(elapsed_prof * 1e3 / args.steps, 4),
         "exact_rounding_fallbacks": fallbacks,
