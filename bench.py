@@ -114,12 +114,20 @@ def time_network(name, spec, in_shape, n, k, w_bound, torch, binding, network, g
         if r:                                      # the first evaluation allocates scratch and feature maps
             times.append(time.perf_counter() - t0)
         del out
+    # one more evaluation with per-launch events: where the time goes, by kernel class
+    ctx.reset_stats()
+    ctx.set_profile(True)
+    out = plan.run(ctx, cts)
+    torch.cuda.synchronize()
+    kernel_ms = {name: round(ms, 2) for name, (_l, _b, ms) in ctx.profile().items() if ms > 0}
+    ctx.set_profile(False)
+    del out
     ctx.close()
     torch.cuda.empty_cache()
     n_mul, n_sq = network.op_counts(spec, in_shape)
     sec = sorted(times)[len(times) // 2]
     return dict(n=n, k=k, k_aux=len(p), inputs=n_in, squarings=n_sq, scalar_products_dense=n_mul,
-                seconds=round(sec, 4), squarings_per_s=round(n_sq / sec, 1))
+                seconds=round(sec, 4), squarings_per_s=round(n_sq / sec, 1), kernel_ms=kernel_ms)
 
 
 def main():
