@@ -311,3 +311,39 @@ def check_small_network(backend, seed_id=1):
         got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], final[o]), n, s.t).astype(np.int64)
         assert np.array_equal(got, want[o]), ("network output", o)
     s.ctx.close()
+
+
+def check_crt_channels(backend, seed_id=1):
+    """Plaintext-space CRT decomposition (Sec. 3.1.2): the same integer computation run as independent
+    channels with coprime plaintext moduli t_1, t_2 (the first two of the CIFAR-10 parameter set), then
+    recombined.  A fully connected node and a square whose true integer results exceed either modulus but
+    not half their product: every channel's ciphertexts equal the oracle's residue by residue, each
+    channel decrypts to the result mod t_i, and the CRT map returns the integers themselves."""
+    n, k = 1024, 4
+    ts = (2424833, 2654209)
+    n_in, n_out = 9, 2
+    rng = gen.rng_for(seed_id, 21)
+    slots = rng.integers(0, 256, size=(n_in, n)).astype(np.int64)          # the same integers in every channel
+    weights = gen.int_weights(rng, (n_out, n_in), 15)
+    idx = layers.fc_index_table(n_in)
+    wt = layers.fc_weight_table(weights)
+    true = (weights.astype(np.int64) @ slots) ** 2                           # over Z: up to (9*15*255)^2 ~ 1.2e9
+    assert int(true.max()) > max(ts) and 2 * int(true.max()) < ts[0] * ts[1]
+    residues = []
+    for ch, t in enumerate(ts):
+        s = Setup(backend, n, k, t=t, seed_id=seed_id, stream=22 + ch)
+        s.ctx.set_relin_key(backend.dev(s.evk))
+        er = gen.encryption_randomness(s.rng, n, n_in)
+        polys = np.stack([fv.slot_encode(slots[i] % t, n, t) for i in range(n_in)])
+        cts = np.stack([fv.encrypt(s.octx, s.pk, polys[i], er["u"][i], er["e1"][i], er["e2"][i]) for i in range(n_in)])
+        mac = s.ctx.ct_scalar_mac(backend.dev(cts), backend.dev(idx), backend.dev(wt), 15)
+        got = backend.host(s.ctx.ct_square_relin(mac.reshape((n_out, 2, k, n))))
+        want = np.stack([fv.square_relin(s.octx, fv.scalar_mac(s.octx, cts, idx[0], wt[0, o]), s.evk) for o in range(n_out)])
+        assert np.array_equal(got, want), ("channel ciphertexts", t)
+        dec = np.stack([fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], got[o]), n, t) for o in range(n_out)]).astype(np.int64)
+        assert np.array_equal(dec, true % t), ("channel plaintext", t)
+        residues.append(dec)
+        s.ctx.close()
+    for o in range(n_out):
+        for j in range(0, n, 37):
+            assert fv.crt_reconstruct([int(residues[0][o, j]), int(residues[1][o, j])], list(ts)) == int(true[o, j])

@@ -91,5 +91,9 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_plaintext_crt_channels(backend):
+    pc.check_crt_channels(backend)
+
+
 def test_small_network_layer_by_layer(backend):
     pc.check_small_network(backend)

@@ -104,6 +104,11 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_plaintext_crt_channels(backend):
+    say("two plaintext moduli of the CIFAR-10 parameter set as CRT channels")
+    pc.check_crt_channels(backend)
+
+
 def test_small_network_layer_by_layer(backend):
     say("miniature network (padded conv, square, pooling, fully connected), every layer against the oracle")
     pc.check_small_network(backend)
