@@ -81,6 +81,64 @@ def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
                 squarings=int(flat.shape[0]), squarings_per_s=round(flat.shape[0] / (sq * 1e-3), 1))
 
 
+def time_primitives(n, k, torch, binding, gen, batch=64, reps=30):
+    """The FHE primitives of the paper's micro-benchmark table (Sec. 5.3: KeyGen, Enc, Dec, HAdd, HSquare,
+    HMultPlain, HMult) at one of its parameter sizes, t = 65537: microseconds per operation when issued one at a
+    time (back to back on one stream) and when issued as one call over a batch.  Randomness is supplied by the
+    caller (already on the device)."""
+    import numpy as np
+    t = 65537
+    q, p = binding.choose_moduli(n, k, t)
+    ctx = binding.Context(n, q, p, t, device="cuda:0")
+    rng = gen.rng_for(2, 9)
+    kr = gen.key_randomness(rng, q, n)
+    dev = ctx.to_device
+    d_kr = {name: dev(v) for name, v in kr.items()}
+    pk, evk = ctx.keygen(d_kr["s"], d_kr["a"], d_kr["e"], d_kr["a_evk"], d_kr["e_evk"])
+    ctx.set_relin_key(evk)
+    er = gen.encryption_randomness(rng, n, batch)
+    d_er = {name: dev(v) for name, v in er.items()}
+    m = dev(rng.integers(0, t, size=(batch, n), dtype=np.int64).astype(np.uint32))
+    cts = ctx.encrypt(pk, m, d_er["u"], d_er["e1"], d_er["e2"])
+    one = lambda x: x[:1]
+    idx1, w1 = dev(np.zeros((1, 1), dtype=np.uint32)), dev(np.full((1, 1, 1), 7, dtype=np.int32))
+    idx2, w2 = dev(np.array([[0, 1]], dtype=np.uint32)), dev(np.ones((1, 1, 2), dtype=np.int32))
+    idxb = dev(np.arange(batch, dtype=np.uint32)[:, None].copy())
+    wb = dev(np.full((batch, 1, 1), 7, dtype=np.int32))
+    idxa = dev(np.stack([np.arange(batch), (np.arange(batch) + 1) % batch], axis=1).astype(np.uint32))
+    wa = dev(np.ones((batch, 1, 2), dtype=np.int32))
+    out1 = torch.empty_like(cts[:1]); outb = torch.empty_like(cts)
+    mac1 = torch.empty((1, 1) + tuple(cts.shape[1:]), dtype=torch.int32, device=ctx.device)
+    macb = torch.empty((1, batch) + tuple(cts.shape[1:]), dtype=torch.int32, device=ctx.device)
+    ops = {
+        "keygen": (lambda: ctx.keygen(d_kr["s"], d_kr["a"], d_kr["e"], d_kr["a_evk"], d_kr["e_evk"]), None),
+        "encrypt": (lambda: ctx.encrypt(pk, one(m), one(d_er["u"]), one(d_er["e1"]), one(d_er["e2"])),
+                    lambda: ctx.encrypt(pk, m, d_er["u"], d_er["e1"], d_er["e2"])),
+        "decrypt": (lambda: ctx.decrypt(d_kr["s"], cts[:1]), lambda: ctx.decrypt(d_kr["s"], cts)),
+        "hadd": (lambda: ctx.ct_scalar_mac(cts, idx2, w2, 1, out=mac1), lambda: ctx.ct_scalar_mac(cts, idxa, wa, 1, out=macb)),
+        "hmultplain": (lambda: ctx.ct_scalar_mac(cts, idx1, w1, 7, out=mac1), lambda: ctx.ct_scalar_mac(cts, idxb, wb, 7, out=macb)),
+        "hsquare": (lambda: ctx.ct_square_relin(cts[:1], out=out1), lambda: ctx.ct_square_relin(cts, out=outb)),
+        "hmult": (lambda: ctx.ct_mul_relin(cts[:1], cts[1:2], out=out1), lambda: ctx.ct_mul_relin(cts, cts.roll(1, 0).contiguous(), out=outb)),
+    }
+    res = {}
+    for name, (single, batched) in ops.items():
+        row = {}
+        for label, fn, div in (("single_us", single, 1), ("batched_us_per_op", batched, batch)):
+            if fn is None:
+                continue
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            row[label] = round((time.perf_counter() - t0) / reps / div * 1e6, 2)
+        res[name] = row
+    ctx.close()
+    return dict(n=n, k=k, k_aux=len(p), batch=batch, ops=res)
+
+
 def time_network(name, spec, in_shape, n, k, t, w_bound, torch, binding, network, gen, reps=2):
     """A whole HCNN-shaped network (architecture tables of Sec. 3.2) at a ring degree and modulus size of the
     paper's parameter table, one plaintext channel, random ciphertexts and random integer weights resident in
@@ -139,6 +197,7 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
     ap.add_argument("--no-layers", action="store_true", help="skip the conv-layer timings (configs 3 and 4)")
     ap.add_argument("--no-networks", action="store_true", help="skip the whole-network timings")
+    ap.add_argument("--no-primitives", action="store_true", help="skip the per-primitive latencies")
     ap.add_argument("--relin-order", type=int, default=0, help="HCNN_OPT_RELIN_ORDER (tuning experiments)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain device copy of 256 MiB (a reference dispatch for HBM byte counters)")
@@ -281,6 +340,12 @@ def main():
         networks_out["cifar10-hcnn-n16384"] = time_network("cifar10", network.CIFAR10_HCNN, network.CIFAR10_INPUT,
                                                            16384, 12, 65537, 7, torch, binding, network, gen)
 
+    # ---- the primitives of the paper's micro-benchmark table at its parameter sizes 2 and 4 (360-bit q)
+    primitives_out = {}
+    if not args.no_primitives:
+        primitives_out["n8192-q360"] = time_primitives(8192, 12, torch, binding, gen)
+        primitives_out["n16384-q360"] = time_primitives(16384, 12, torch, binding, gen)
+
     # ---- CPU oracle on a bounded sample of the same squarings (also a parity check)
     cpu = None
     if not args.no_cpu_baseline:
@@ -320,10 +385,15 @@ def main():
         "cpu_baseline": cpu,
         "conv_layers": layers_out,
         "networks": networks_out,
+        "primitives": primitives_out,
         "kernels": kernels,
         "profiled_pass_ms_per_step": None if elapsed_prof is None else round(elapsed_prof * 1e3 / args.steps, 4),
         "exact_rounding_fallbacks": fallbacks,
-        "context": {"paper_hsquare_ms_v100": 1.679, "paper_mnist_s_v100": 5.16,
+        "context": {"paper_primitives_ms_v100_sets_2_and_4": {"keygen": [12.377, 21.392], "encrypt": [0.935, 1.496],
+                                                              "decrypt": [0.075, 0.098], "hadd": [0.052, 0.054],
+                                                              "hsquare": [1.679, 2.371], "hmultplain": [0.033, 0.035],
+                                                              "hmult": [2.014, 2.769]},
+                    "paper_hsquare_ms_v100": 1.679, "paper_mnist_s_v100": 5.16,
                     "paper_cifar10_s_1gpu_per_channel": 553.89, "paper_cifar10_s_4gpu_per_channel": 304.43},
     }
     print(json.dumps(line))

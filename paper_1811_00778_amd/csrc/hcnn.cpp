@@ -475,7 +475,7 @@ int ext_dispatch(hcnn_ctx* c, size_t grid, const ExtArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_EXT_CASE(K, KP) \
   if (k == K && kp == KP) return run<ExtKernelT<K, KP>>(c, grid, ExtKernelT<K, KP>::lds_bytes(), a);
-  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(10, 12) HCNN_EXT_CASE(11, 12) HCNN_EXT_CASE(12, 14) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
+  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(10, 12) HCNN_EXT_CASE(11, 12) HCNN_EXT_CASE(12, 13) HCNN_EXT_CASE(12, 14) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
 #undef HCNN_EXT_CASE
   return run<ExtKernel>(c, grid, ExtKernel::lds_bytes(k), a);
 }
@@ -484,7 +484,7 @@ int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_SCALE_CASE(K, KP) \
   if (k == K && kp == KP) return run<ScaleKernelR<K, KP>>(c, grid, ScaleKernelR<K, KP>::lds_bytes(), a);
-  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(10, 12) HCNN_SCALE_CASE(11, 12) HCNN_SCALE_CASE(12, 14) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
+  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(10, 12) HCNN_SCALE_CASE(11, 12) HCNN_SCALE_CASE(12, 13) HCNN_SCALE_CASE(12, 14) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
 #undef HCNN_SCALE_CASE
   return run<ScaleKernel>(c, grid, ScaleKernel::lds_bytes(k, kp), a);
 }
