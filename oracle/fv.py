@@ -337,6 +337,27 @@ def decrypt(ctx: Context, s, ct):
     return np.array([round_div(ctx.t * xi, ctx.Q) % ctx.t for xi in x], dtype=np.uint32)
 
 
+def noise_bits(ctx: Context, s, ct) -> int:
+    """Size of the noise in a ciphertext: with x = [c0 + c1 s]_q, t*x = q*(m + t*a) + r for the centred
+    remainder r = [t*x]_q, and v = r/q is the invariant noise of the ciphertext (Decrypt of Sec. 2.1
+    returns m exactly while |v| < 1/2; the noise budget of Sec. 5.5 is -log2(2 max|v|), i.e.
+    log2(q) - 1 - log2(max|r|)).  Returns the bit length of max_j |r_j| (0 when every r_j = 0)."""
+    s_r = ctx.small_to_rns(s)
+    x = ctx.lift(ctx.add_rq(_as_u32(ct[0]), ctx.mul_rq(ct[1], s_r)))
+    worst = 0
+    for xi in x:
+        r = centre(ctx.t * xi % ctx.Q, ctx.Q)
+        worst = max(worst, abs(r))
+    return int(worst).bit_length()
+
+
+def noise_budget_bits(ctx: Context, bits: int) -> float:
+    """Noise budget in bits for a noise of `bits` bits: log2(q) - 1 - bits, a lower bound that is less
+    than one bit below -log2(2 max|v|)."""
+    import math
+    return math.log2(ctx.Q) - 1 - bits
+
+
 def hmult_scaled(ctx: Context, ct1, ct2):
     """HMult steps 1 and the scaling of step 2 (Sec. 2.1): the tensor over the integers on
     centred lifts, then round(t/q * .) per coefficient, reduced mod q.  Returns [3][k][n]."""
