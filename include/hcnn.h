@@ -163,6 +163,16 @@ int hcnn_encrypt(hcnn_ctx* ctx, const uint32_t* pk_dev, const uint32_t* m_dev, c
 int hcnn_decrypt(hcnn_ctx* ctx, const int32_t* sk_dev, const uint32_t* ct_dev, size_t n_ct,
                  uint32_t* m_out_dev);
 
+/* Noise read-out (the quantity behind the noise-budget figure of Sec. 5.5): with x = [c0 + c1*s]_q,
+ * t*x = q*(m + t*a) + r for the centred remainder r = [t*x]_q; r/q is the invariant noise and Decrypt
+ * returns m while |r/q| < 1/2.  bits_out_dev[i] = bit length of max_j |r_j| of ciphertext i (0 when every
+ * r_j is 0), computed exactly; the noise budget in bits is log2(q) - 1 - bits (within one bit).
+ *   sk_dev int32[n]; ct_dev uint32[n_ct][2][k][n] (16-byte aligned); bits_out_dev uint32[n_ct] (device,
+ *   overwritten; cleared with a memset on the context's stream, so the call is not for graph capture).
+ *   Returns HCNN_OK, HCNN_ERR_NULL, HCNN_ERR_ALIGN, or a HIP error code. */
+int hcnn_noise_bits(hcnn_ctx* ctx, const int32_t* sk_dev, const uint32_t* ct_dev, size_t n_ct,
+                    uint32_t* bits_out_dev);
+
 /* ---- diagnostics ---------------------------------------------------------------------- */
 enum {
   HCNN_STAT_EXACT_FALLBACKS = 0, /* coefficients whose base conversion needed the exact

@@ -28,6 +28,7 @@ SIGNATURES = {
     "hcnn_keygen": [ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr],
     "hcnn_encrypt": [ptr, ptr, ptr, ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_decrypt": [ptr, ptr, ptr, C.c_size_t, ptr],
+    "hcnn_noise_bits": [ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_get_stat": [ptr, C.c_int, u64p],
     "hcnn_reset_stats": [ptr],
     "hcnn_set_option": [ptr, C.c_int, C.c_uint64],

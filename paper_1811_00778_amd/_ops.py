@@ -120,6 +120,15 @@ class OpsMixin:
         self.raw.call("hcnn_decrypt", self._ptr(sk), self._ptr(cts), n_ct, self._ptr(out))
         return out
 
+    def noise_bits(self, sk, cts):
+        """Bit length of the largest centred remainder of t*(c0 + c1*s) mod q per ciphertext (hcnn_noise_bits);
+        the noise budget is log2(q) - 1 - bits."""
+        self._check(sk, "i32"); self._check(cts, "u32")
+        n_ct = self._count(cts, self.ct_shape)
+        out = self._empty((n_ct,), "u32")
+        self.raw.call("hcnn_noise_bits", self._ptr(sk), self._ptr(cts), n_ct, self._ptr(out))
+        return out
+
     # ---- diagnostics
     def exact_fallbacks(self):
         return self.raw.stat(_capi.STAT_EXACT_FALLBACKS)

@@ -758,4 +758,68 @@ struct DecRoundKernel {
   }
 };
 
+// Noise read-out: x [count][k][n] (c0 + c1*s mod q) -> bits[count] = bit length of max_j |r_j|, r = [t*x]_q centred.
+// Exact: the residues of the non-negative remainder R = t*x mod q are turned into mixed-radix digits, R > (q-1)/2
+// is decided on the digits, |r| = R or q - R is rebuilt as a multiword integer by Horner's rule on the digits, and its
+// bit length is folded into the ciphertext's maximum.  bits[] must be zero on entry.
+struct NoiseArgs {
+  const uint32_t* x;
+  uint32_t* bits;
+  BConvDev bc;             // src q with xmul = t (the table of the decrypt rounding)
+  uint32_t n;
+};
+struct NoiseKernel {
+  static constexpr int kThreads = kEwThreads;
+  static constexpr int kPhases = 1;
+  struct Regs {};
+  static size_t lds_bytes(uint32_t ks) { return (size_t)2 * ks * kThreads * 4; }
+  template <int PH>
+  HCNN_HD static void phase(const NoiseArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+    const uint32_t ks = a.bc.ks, n = a.n;
+    const uint32_t per_poly = n / kThreads;
+    const size_t poly = bid / per_poly;
+    const uint32_t c = (bid % per_poly) * kThreads + tid;
+    const uint32_t* src = a.x + poly * ks * n + c;
+    uint32_t* dig = lds + tid;                                   // mixed-radix digits
+    uint32_t* word = lds + (size_t)ks * kThreads + tid;          // multiword |r|, least significant first
+    for (uint32_t i = 0; i < ks; ++i)
+      dig[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i).p);
+    if (garner_gt_half(a.bc, dig, kThreads)) {
+      // digits of q - R: zero while the lower digits of R are zero, q_i - d_i at the first non-zero digit,
+      // q_i - 1 - d_i above it
+      bool low_zero = true;
+      for (uint32_t i = 0; i < ks; ++i) {
+        const uint32_t d = dig[i * kThreads], qi = ldc(a.bc.src_mod, i).p;
+        if (low_zero) {
+          if (d != 0) { dig[i * kThreads] = qi - d; low_zero = false; }
+        } else {
+          dig[i * kThreads] = qi - 1 - d;
+        }
+      }
+    }
+    // value = d_0 + q_0*(d_1 + q_1*(d_2 + ...)): Horner from the top digit; it stays below q < 2^(30 ks)
+    for (uint32_t w = 0; w < ks; ++w) word[w * kThreads] = 0;
+    for (int i = (int)ks - 1; i >= 0; --i) {
+      uint64_t carry = dig[i * kThreads];
+      const uint64_t qi = ldc(a.bc.src_mod, (uint32_t)i).p;
+      for (uint32_t w = 0; w < ks; ++w) {
+        const uint64_t v = (uint64_t)word[w * kThreads] * qi + carry;
+        word[w * kThreads] = (uint32_t)v;
+        carry = v >> 32;
+      }
+    }
+    uint32_t bits = 0;
+    for (int w = (int)ks - 1; w >= 0; --w) {
+      uint32_t v = word[w * kThreads];
+      if (v != 0) {
+        uint32_t len = 0;
+        while (v) { ++len; v >>= 1; }
+        bits = 32u * (uint32_t)w + len;
+        break;
+      }
+    }
+    if (bits) atomic_max32(a.bits + poly, bits);
+  }
+};
+
 }  // namespace hcnn

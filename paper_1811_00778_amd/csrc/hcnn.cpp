@@ -873,6 +873,40 @@ int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct
   return HCNN_OK;
 }
 
+int hcnn_noise_bits(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint32_t* bits_out) {
+  if (!c || !sk || !ct || !bits_out) return HCNN_ERR_NULL;
+  if (!aligned16(ct)) return HCNN_ERR_ALIGN;
+  if (n_ct == 0) return HCNN_OK;
+  const uint32_t k = c->k, n = c->n;
+  const size_t rn = n, poly = (size_t)k * rn;
+  const size_t bpp = n / kEwThreads;
+  const size_t C = std::min<size_t>(n_ct, 64);
+  // scratch: s_hat [k][n] | x [C][k][n]
+  int e = ensure_scratch(c, (poly + C * poly) * 4);
+  if (e) return e;
+  uint32_t* s_hat = c->scratch;
+  uint32_t* x = s_hat + poly;
+  if ((e = dev_memset(bits_out, 0, n_ct * sizeof(uint32_t), c->stream))) return e;
+  SmallToRnsArgs sr{sk, s_hat, c->d_mods, k, n};
+  if ((e = run<SmallToRnsKernel>(c, bpp, 0, sr))) return e;
+  if ((e = ntt_dense(c, s_hat, s_hat, k, k, false))) return e;
+  for (size_t c0 = 0; c0 < n_ct; c0 += C) {
+    const size_t cc = std::min(C, n_ct - c0);
+    const uint32_t* cts = ct + c0 * 2 * poly;
+    NttRows r{cts, x, cc * k, k, 0, 2 * k, k, k, 0};            // x = NTT(c1) of every ciphertext
+    if ((e = ntt_rows(c, r, false))) return e;
+    PointMulArgs pm{x, s_hat, x, c->d_mods, k, n, (uint32_t)(cc * k), k, 0u};
+    if ((e = run<PointMulKernel>(c, cc * k * bpp, 0, pm))) return e;
+    if ((e = ntt_dense(c, x, x, cc * k, k, true))) return e;
+    AddRowsArgs ar{cts, x, x, c->d_mods, k, n, 2 * k, 0u};
+    if ((e = run<AddRowsKernel>(c, cc * k * bpp, 0, ar))) return e;
+    NoiseArgs na;
+    na.x = x; na.bits = bits_out + c0; na.bc = c->dec; na.n = n;
+    if ((e = run<NoiseKernel>(c, cc * bpp, NoiseKernel::lds_bytes(k), na))) return e;
+  }
+  return HCNN_OK;
+}
+
 // ---------------------------------------------------------------- diagnostics
 int hcnn_get_stat(hcnn_ctx* c, int which, uint64_t* out) {
   if (!c || !out) return HCNN_ERR_NULL;

@@ -82,6 +82,7 @@ inline int event_record(hcnn_event_t, hcnn_stream_t) { return 0; }
 inline int event_elapsed_ms(float* ms, hcnn_event_t, hcnn_event_t) { *ms = 0.f; return 0; }
 inline size_t max_lds_bytes() { return 160 * 1024; }
 HCNN_HD void atomic_inc64(unsigned long long* p) { *p += 1; }
+HCNN_HD void atomic_max32(uint32_t* p, uint32_t v) { if (v > *p) *p = v; }
 
 template <class K, int PH>
 struct EmuPhases {
@@ -132,6 +133,7 @@ inline size_t max_lds_bytes() {
   return (size_t)v;
 }
 HCNN_HD void atomic_inc64(unsigned long long* p) { atomicAdd(p, 1ull); }
+HCNN_HD void atomic_max32(uint32_t* p, uint32_t v) { atomicMax(p, v); }
 
 template <class K, int PH, class Args>
 __device__ __forceinline__ void run_phases(const Args& a, unsigned bid, int tid, uint32_t* lds,

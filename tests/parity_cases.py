@@ -347,3 +347,24 @@ def check_crt_channels(backend, seed_id=1):
     for o in range(n_out):
         for j in range(0, n, 37):
             assert fv.crt_reconstruct([int(residues[0][o, j]), int(residues[1][o, j])], list(ts)) == int(true[o, j])
+
+
+def check_noise_bits(backend, n, k, seed_id=1):
+    """hcnn_noise_bits against the oracle's exact read-out: fresh ciphertexts, a weighted sum, its square, a
+    noise-free ciphertext, the zero ciphertext and noise-saturated (uniformly random) ones."""
+    s = Setup(backend, n, k, seed_id=seed_id, stream=31)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    slots, polys, er, cts = s.encrypt_oracle(4, high=256)
+    w = np.array([[[3, -2, 1, 5]]], dtype=np.int32)
+    idx = np.arange(4, dtype=np.uint32)[None, :]
+    mac = s.ctx.ct_scalar_mac(backend.dev(cts), backend.dev(idx), backend.dev(w), 5)
+    sq = s.ctx.ct_square_relin(mac.reshape((1, 2, k, n)))
+    flat = np.stack([s.octx.to_rns([(s.octx.Q // s.t) * int(v) for v in polys[0]]), np.zeros((k, n), dtype=np.uint32)])
+    rnd = gen.uniform_residues(s.rng, s.q, n, lead=(2, 2))
+    batch = np.concatenate([cts, backend.host(mac).reshape((1, 2, k, n)), backend.host(sq),
+                            flat[None], np.zeros((1, 2, k, n), dtype=np.uint32), rnd])
+    got = backend.host(s.ctx.noise_bits(backend.dev(s.kr["s"]), backend.dev(batch)))
+    want = np.array([fv.noise_bits(s.octx, s.kr["s"], batch[i]) for i in range(batch.shape[0])], dtype=np.uint32)
+    assert np.array_equal(got, want), (got, want)
+    assert want[7] == 0 and want[4] > want[0] and want[5] > want[4], want   # zero; sum noisier than fresh; square noisier
+    s.ctx.close()

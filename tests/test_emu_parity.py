@@ -91,6 +91,11 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_noise_read_out(backend):
+    pc.check_noise_bits(backend, 1024, 2)
+    pc.check_noise_bits(backend, 1024, 5)
+
+
 def test_plaintext_crt_channels(backend):
     pc.check_crt_channels(backend)
 

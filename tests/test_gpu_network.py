@@ -64,6 +64,19 @@ def test_mnist_network_end_to_end():
     for o in range(10):
         got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[o]), n, t).astype(np.int64)
         assert np.array_equal(got, want[o]), ("network output", o)
+
+    # noise budget after every layer (the quantity plotted in the noise-growth figure of Sec. 5.5): read out on the
+    # GPU for every ciphertext of every layer, checked against the oracle on the first ciphertext of each layer
+    d_sk = dev(s.kr["s"])
+    _, kept = plan.run(ctx, cts, keep=True)
+    stages = [("fresh", cts)] + [(layer[0], a) for layer, a in zip(network.MNIST_HCNN, kept)]
+    budgets = []
+    for name, a in stages:
+        bits = backend.host(ctx.noise_bits(d_sk, a))
+        assert int(bits[0]) == fv.noise_bits(s.octx, s.kr["s"], backend.host(a[:1])[0]), ("noise read-out", name)
+        budgets.append(fv.noise_budget_bits(s.octx, int(bits.max())))
+        say("noise budget after %-6s (%4d ciphertexts): %6.1f bits" % (name, a.shape[0], budgets[-1]))
+    assert all(b1 > b2 for b1, b2 in zip(budgets, budgets[1:])) and budgets[-1] > 0
     ctx.close()
 
 

@@ -104,6 +104,13 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_noise_read_out(backend):
+    say("noise read-out n=1024 k=2, n=2048 k=5, n=8192 k=8")
+    pc.check_noise_bits(backend, 1024, 2)
+    pc.check_noise_bits(backend, 2048, 5)
+    pc.check_noise_bits(backend, 8192, 8, seed_id=2)
+
+
 def test_plaintext_crt_channels(backend):
     say("two plaintext moduli of the CIFAR-10 parameter set as CRT channels")
     pc.check_crt_channels(backend)
