@@ -57,6 +57,13 @@ class Context(OpsMixin):
         stream = torch.cuda.current_stream(self.device).cuda_stream
         self.raw = _capi.RawContext(lib(), n, q_primes, p_primes, t, stream)
 
+    def use_stream(self, stream=None):
+        """Launch on `stream` (a torch.cuda.Stream; default: torch's current stream) from now on
+        (hcnn_set_stream).  After one warm-up call per operation and size, the hot-path calls allocate nothing
+        and enqueue kernels only, so they can be recorded into a HIP graph on the stream given here."""
+        stream = torch.cuda.current_stream(self.device) if stream is None else stream
+        self.raw.call("hcnn_set_stream", ctypes.c_void_p(stream.cuda_stream))
+
     def _ptr(self, x):
         return ctypes.c_void_p(x.data_ptr())
 

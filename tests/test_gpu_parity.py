@@ -104,6 +104,43 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_hot_path_under_graph_capture(backend):
+    """Scalar MAC + squaring recorded into a HIP graph on a side stream and replayed: every replay, with eager
+    work and synchronisations between the replays, must reproduce the eager result bit for bit."""
+    import torch
+    say("graph capture of scalar MAC + squaring, three replays")
+    n, k = 4096, 4
+    s = pc.Setup(backend, n, k, seed_id=2, stream=41)
+    ctx, dev = s.ctx, backend.dev
+    ctx.set_relin_key(dev(s.evk))
+    cts = dev(gen.uniform_residues(s.rng, s.q, n, lead=(6, 2)))
+    idx = dev(np.array([[0, 1, 2], [3, 4, 5]], dtype=np.uint32))
+    w = dev(np.array([[[1, -2, 3], [4, 5, -6]], [[-7, 8, 9], [1, 1, 1]]], dtype=np.int32))
+    eager_mac = ctx.ct_scalar_mac(cts, idx, w, 9)
+    eager_sq = ctx.ct_square_relin(eager_mac.reshape((4, 2, k, n)))
+    want = np.stack([fv.square_relin(s.octx, backend.host(eager_mac.reshape((4, 2, k, n)))[i], s.evk) for i in (0, 3)])
+    assert np.array_equal(backend.host(eager_sq)[[0, 3]], want)
+    g_mac, g_sq = torch.zeros_like(eager_mac), torch.zeros_like(eager_sq)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        ctx.use_stream(side)
+        ctx.ct_square_relin(ctx.ct_scalar_mac(cts, idx, w, 9, out=g_mac).reshape((4, 2, k, n)), out=g_sq)   # warm-up
+    side.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        ctx.ct_square_relin(ctx.ct_scalar_mac(cts, idx, w, 9, out=g_mac).reshape((4, 2, k, n)), out=g_sq)
+    ctx.use_stream()
+    for rep in range(3):
+        g_mac.zero_(); g_sq.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g_mac, eager_mac) and torch.equal(g_sq, eager_sq), ("replay", rep)
+        ctx.ct_square_relin(cts[rep:rep + 2])                     # eager work between the replays
+        torch.cuda.synchronize()
+    ctx.close()
+
+
 def test_noise_read_out(backend):
     say("noise read-out n=1024 k=2, n=2048 k=5, n=8192 k=8")
     pc.check_noise_bits(backend, 1024, 2)
