@@ -129,3 +129,52 @@ class Plan:
             if keep:
                 kept.append(cts)
         return (cts, kept) if keep else cts
+
+
+def _main(argv=None):
+    """python -m paper_1811_00778_amd.network {mnist,cifar10} [--n N] [--k K] [--t T] [--reps R]
+    Times one evaluation of the network on random ciphertexts, random integer weights and a random (not
+    genuine) evaluation key, all resident on the GPU; meant for profiling runs."""
+    import argparse
+    import time
+
+    import torch
+
+    from . import binding
+    ap = argparse.ArgumentParser(prog="python -m paper_1811_00778_amd.network")
+    ap.add_argument("name", choices=("mnist", "cifar10"))
+    ap.add_argument("--n", type=int, default=8192)
+    ap.add_argument("--k", type=int, default=0, help="30-bit primes in q (default: 11 for mnist, 10 for cifar10)")
+    ap.add_argument("--t", type=int, default=0, help="plaintext modulus (default: 65537 / 2424833)")
+    ap.add_argument("--reps", type=int, default=2)
+    args = ap.parse_args(argv)
+    spec, in_shape = (MNIST_HCNN, MNIST_INPUT) if args.name == "mnist" else (CIFAR10_HCNN, CIFAR10_INPUT)
+    k = args.k or (11 if args.name == "mnist" else 10)
+    t = args.t or (65537 if args.name == "mnist" else 2424833)
+    q, p = binding.choose_moduli(args.n, k, t)
+    ctx = binding.Context(args.n, q, p, t)
+    gen = torch.Generator(device=ctx.device)
+    gen.manual_seed(1811)
+    rnd = lambda *shape: torch.randint(0, 1 << 29, shape, dtype=torch.int32, device=ctx.device, generator=gen)
+    ctx.set_relin_key(rnd(k, 2, k, args.n))
+    rng = np.random.default_rng(1811)
+    bound = 15 if args.name == "mnist" else 7
+    weights = [None if s is None else rng.integers(-bound, bound + 1, size=s).astype(np.int32)
+               for s in weight_shapes(spec, in_shape)]
+    plan = Plan(spec, in_shape, weights, ctx.to_device)
+    cts = rnd(in_shape[0] * in_shape[1] * in_shape[2], 2, k, args.n)
+    n_mul, n_sq = op_counts(spec, in_shape)
+    for r in range(args.reps + 1):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = plan.run(ctx, cts)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        print("%s n=%d k=%d k_aux=%d t=%d: evaluation %d%s %.4f s (%d squarings, %d scalar products)"
+              % (args.name, args.n, k, len(p), t, r, " (cold)" if r == 0 else "", dt, n_sq, n_mul), flush=True)
+        del out
+    ctx.close()
+
+
+if __name__ == "__main__":
+    _main()
