@@ -190,10 +190,10 @@ def time_network(name, spec, in_shape, n, k, t, w_bound, torch, binding, network
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=3, help="squarings the oracle computes for cpu_baseline")
+    ap.add_argument("--cpu-sample", type=int, default=12, help="squarings the oracle computes for cpu_baseline")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
     ap.add_argument("--no-layers", action="store_true", help="skip the conv-layer timings (configs 3 and 4)")
     ap.add_argument("--no-networks", action="store_true", help="skip the whole-network timings")

@@ -376,13 +376,19 @@ struct RelinMacKernel {
     const Mod m = ldc(a.mods, j);
     const size_t rn = a.n;
     uint64_t s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
-    for (uint32_t i = 0; i < a.k; ++i) {
-      const U4 d = *reinterpret_cast<const U4*>(a.dig + ((ct * a.k + i) * a.k + j) * rn + c);
-      const U4 e0 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 0) * a.k + j) * rn + c);
-      const U4 e1 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 1) * a.k + j) * rn + c);
-      s0[0] += (uint64_t)d.x * e0.x; s0[1] += (uint64_t)d.y * e0.y; s0[2] += (uint64_t)d.z * e0.z; s0[3] += (uint64_t)d.w * e0.w;
-      s1[0] += (uint64_t)d.x * e1.x; s1[1] += (uint64_t)d.y * e1.y; s1[2] += (uint64_t)d.z * e1.z; s1[3] += (uint64_t)d.w * e1.w;
-      if ((i % 15u) == 14u && i + 1 < a.k) {             // 15 products below 2^60 (+ a residue) fit 64 bits
+    // 15 products below 2^60 (+ a residue) fit 64 bits; inside a run of 15 the loop is unrolled so that the
+    // loads of several digits are in flight together
+    for (uint32_t i0 = 0; i0 < a.k; i0 += 15) {
+      const uint32_t i1 = i0 + 15 < a.k ? i0 + 15 : a.k;
+#pragma unroll 4
+      for (uint32_t i = i0; i < i1; ++i) {
+        const U4 d = *reinterpret_cast<const U4*>(a.dig + ((ct * a.k + i) * a.k + j) * rn + c);
+        const U4 e0 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 0) * a.k + j) * rn + c);
+        const U4 e1 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 1) * a.k + j) * rn + c);
+        s0[0] += (uint64_t)d.x * e0.x; s0[1] += (uint64_t)d.y * e0.y; s0[2] += (uint64_t)d.z * e0.z; s0[3] += (uint64_t)d.w * e0.w;
+        s1[0] += (uint64_t)d.x * e1.x; s1[1] += (uint64_t)d.y * e1.y; s1[2] += (uint64_t)d.z * e1.z; s1[3] += (uint64_t)d.w * e1.w;
+      }
+      if (i1 < a.k) {
         for (int q = 0; q < 4; ++q) { s0[q] = reduce64(s0[q], m); s1[q] = reduce64(s1[q], m); }
       }
     }
