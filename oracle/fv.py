@@ -334,7 +334,8 @@ def decrypt(ctx: Context, s, ct):
         if comp + 1 < len(ct):
             spow = ctx.mul_rq(spow, s_r)
     x = ctx.lift(acc)
-    return np.array([round_div(ctx.t * xi, ctx.Q) % ctx.t for xi in x], dtype=np.uint32)
+    dtype = np.uint32 if ctx.t < (1 << 32) else np.uint64        # plaintext words: 32 bits unless t needs more
+    return np.array([round_div(ctx.t * xi, ctx.Q) % ctx.t for xi in x], dtype=dtype)
 
 
 def noise_bits(ctx: Context, s, ct) -> int:
@@ -425,9 +426,22 @@ def slot_eval(polys, n: int, t: int, slots):
     """Values of the chosen slots only: polys [m][n] in R_t -> [m][len(slots)], slot j being the value
     of the polynomial at psi_t^(2j+1) (the evaluation view of the plaintext CRT map, Sec. 2.1.1).
     Written as the evaluation itself, for use where only a few slots of many polynomials are needed."""
-    polys = np.asarray(polys, dtype=np.int64) % t
-    assert polys.ndim == 2 and polys.shape[1] == n and t < (1 << 24)
     psi = root_of_unity(n, t)
+    if t >= (1 << 24):
+        # wide plaintext modulus (the 43-bit t of the MNIST parameter sets): Python integers throughout
+        rows = [[int(v) % t for v in row] for row in np.asarray(polys)]
+        assert all(len(r) == n for r in rows)
+        out = np.zeros((len(rows), len(slots)), dtype=object)
+        for col, j in enumerate(slots):
+            x = pow(psi, 2 * int(j) + 1, t)
+            powers = [1] * n
+            for i in range(1, n):
+                powers[i] = powers[i - 1] * x % t
+            for r, row in enumerate(rows):
+                out[r, col] = sum(map(int.__mul__, row, powers)) % t
+        return out
+    polys = np.asarray(polys, dtype=np.int64) % t
+    assert polys.ndim == 2 and polys.shape[1] == n
     out = np.zeros((polys.shape[0], len(slots)), dtype=np.int64)
     for col, j in enumerate(slots):
         x = pow(psi, 2 * int(j) + 1, t)

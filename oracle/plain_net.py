@@ -6,10 +6,17 @@ Tables 1-2: convolution without bias, square activation, average pooling evaluat
 window sum, fully connected layers).  This module writes that computation out with numpy
 integer arrays; it knows nothing of ciphertexts.  Feature maps are [C][H][W][S] for S slots.
 
+For t below 2^31 the arrays are int64 (every intermediate stays far below 2^63); for a wider t (the 43-bit
+modulus of the MNIST parameter sets) they hold Python integers (dtype=object), which cannot overflow.
+
 Layer specs are the tuples used by the network runner:
     ("conv", filters, fh, fw, stride, pad), ("pool", extent), ("fc", n_out), ("square",)
 """
 import numpy as np
+
+
+def _dtype(t):
+    return np.int64 if t < (1 << 31) else object
 
 
 def conv_mod(x, w, stride, pad, t):
@@ -17,15 +24,16 @@ def conv_mod(x, w, stride, pad, t):
     C, H, W, S = x.shape
     F, Cw, fh, fw = w.shape
     assert C == Cw
+    dt = _dtype(t)
     if pad:
-        xp = np.zeros((C, H + 2 * pad, W + 2 * pad, S), dtype=np.int64)
+        xp = np.zeros((C, H + 2 * pad, W + 2 * pad, S), dtype=dt)
         xp[:, pad:pad + H, pad:pad + W] = x
     else:
-        xp = x.astype(np.int64)
+        xp = x.astype(dt)
     ho, wo = (H + 2 * pad - fh) // stride + 1, (W + 2 * pad - fw) // stride + 1
-    y = np.zeros((F, ho, wo, S), dtype=np.int64)
+    y = np.zeros((F, ho, wo, S), dtype=dt)
     for f in range(F):
-        acc = np.zeros((ho, wo, S), dtype=np.int64)
+        acc = np.zeros((ho, wo, S), dtype=dt)
         for c in range(C):
             for dy in range(fh):
                 for dx in range(fw):
@@ -39,7 +47,7 @@ def sum_pool_mod(x, extent, t):
     """Window sums with stride = extent (the division of average pooling is folded into the scale, Sec. 4.3)."""
     C, H, W, S = x.shape
     ho, wo = (H - extent) // extent + 1, (W - extent) // extent + 1
-    y = np.zeros((C, ho, wo, S), dtype=np.int64)
+    y = np.zeros((C, ho, wo, S), dtype=_dtype(t))
     for dy in range(extent):
         for dx in range(extent):
             y += x[:, dy:dy + extent * ho:extent, dx:dx + extent * wo:extent]
@@ -49,17 +57,18 @@ def sum_pool_mod(x, extent, t):
 def fc_mod(x, w, t):
     """y[o] = sum_i w[o, i] * x.flat[i], mod t, inputs flattened in (c, row, column) order."""
     C, H, W, S = x.shape
-    flat = x.reshape(C * H * W, S).astype(np.int64)
-    y = np.zeros((w.shape[0], S), dtype=np.int64)
+    dt = _dtype(t)
+    flat = x.reshape(C * H * W, S).astype(dt)
+    y = np.zeros((w.shape[0], S), dtype=dt)
     step = 1024                           # partial sums of at most 1024 terms stay below 2^63
     for i0 in range(0, flat.shape[0], step):
-        y = (y + w[:, i0:i0 + step].astype(np.int64) @ flat[i0:i0 + step]) % t
+        y = (y + w[:, i0:i0 + step].astype(dt) @ flat[i0:i0 + step]) % t
     return y.reshape(w.shape[0], 1, 1, S)
 
 
 def evaluate(spec, weights, x, t, keep=False):
     """Applies the layers of `spec` to x [C][H][W][S] modulo t; weights[i] belongs to layer i (None if unused)."""
-    x = np.asarray(x, dtype=np.int64) % t
+    x = np.asarray(x, dtype=_dtype(t)) % t
     kept = []
     for layer, w in zip(spec, weights):
         kind = layer[0]
