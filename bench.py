@@ -327,13 +327,12 @@ def main():
             layers_out[gen.CONFIGS[cid]["name"]] = time_layer(cid, torch, binding, layers, gen, relin_order=args.relin_order)
 
     # ---- whole networks at the sizes of the paper's parameter table (Sec. 4.2), one plaintext channel each:
-    #      MNIST set 1 (N = 2^13, 330-bit q; t = 65537 here, the 43-bit t of the paper does not fit this build's
-    #      32-bit plaintext words), CIFAR-10 set 5 (N = 2^13, 300-bit q, t = its first plaintext modulus), and
+    #      MNIST set 1 (N = 2^13, 330-bit q, the 43-bit t = 5522259017729), CIFAR-10 set 5 (N = 2^13, 300-bit q, t = its first plaintext modulus), and
     #      the CIFAR-10 shape again at N = 2^14 with a 360-bit q
     networks_out = {}
     if not args.no_networks:
         from paper_1811_00778_amd import network
-        networks_out["mnist-hcnn"] = time_network("mnist", network.MNIST_HCNN, network.MNIST_INPUT, 8192, 11, 65537, 15,
+        networks_out["mnist-hcnn"] = time_network("mnist", network.MNIST_HCNN, network.MNIST_INPUT, 8192, 11, 5522259017729, 15,
                                                   torch, binding, network, gen)
         networks_out["cifar10-hcnn"] = time_network("cifar10", network.CIFAR10_HCNN, network.CIFAR10_INPUT, 8192, 10,
                                                     2424833, 7, torch, binding, network, gen)

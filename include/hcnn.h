@@ -51,7 +51,8 @@ enum {
   HCNN_ERR_NULL = -1,     /* a required pointer is null                                     */
   HCNN_ERR_N = -2,        /* n is not a power of two in [2^10, 2^15]                        */
   HCNN_ERR_PRIME = -3,    /* a modulus is not a prime in (2^29, 2^30), not 1 mod 2n, or repeated */
-  HCNN_ERR_T = -4,        /* t is not a prime below 2^29, or equals a ciphertext prime      */
+  HCNN_ERR_T = -4,        /* t is not a prime below 2^47, equals a ciphertext or auxiliary prime,
+                             or the call's plaintext word size does not match t            */
   HCNN_ERR_AUX = -5,      /* auxiliary basis too small: needs p_0*...*p_{k'-1} > t*n*q + 1    */
   HCNN_ERR_ARG = -6,      /* a count or size is zero, too large, or inconsistent            */
   HCNN_ERR_NOKEY = -7,    /* hcnn_ct_square_relin before hcnn_set_relin_key                 */
@@ -74,7 +75,7 @@ int hcnn_gen_primes(uint32_t n, uint32_t count, uint32_t* primes_host);
  * q) has product > t*n*q + 1: the range needed to hold the scaled tensor product
  * round(t*c*c'/q) of Sec. 2.1 (HMult step 2) exactly.  HCNN_ERR_AUX if n_candidates
  * do not suffice. */
-int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q_primes_host, uint32_t t,
+int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q_primes_host, uint64_t t,
                        const uint32_t* candidates_host, uint32_t n_candidates, uint32_t* k_aux_out);
 
 /* ---- context ------------------------------------------------------------------------ */
@@ -83,9 +84,13 @@ int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q_primes_host, ui
  * ciphertext primes q_primes_host[0..k), auxiliary primes p_primes_host[0..k_aux) and
  * plaintext modulus t, uploads them to the current HIP device and binds the context
  * to hip_stream (a hipStream_t passed as void*; NULL = the default stream).
- * k_aux may be 0 when hcnn_ct_square_relin is not used. */
+ * k_aux may be 0 when hcnn_ct_square_relin is not used.
+ * t is any prime below 2^47 that is none of the primes above (the parameter table of Sec. 4.2 uses a
+ * 43-bit t for MNIST and ten 22/23-bit moduli, one context each, for CIFAR-10).  Plaintext polynomials
+ * cross the boundary in 32-bit words when t < 2^32 (hcnn_encrypt / hcnn_decrypt) and in 64-bit words
+ * otherwise (hcnn_encrypt_wide / hcnn_decrypt_wide); the other entry points do not depend on the size of t. */
 int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q_primes_host,
-                    uint32_t k_aux, const uint32_t* p_primes_host, uint32_t t, void* hip_stream);
+                    uint32_t k_aux, const uint32_t* p_primes_host, uint64_t t, void* hip_stream);
 int hcnn_ctx_destroy(hcnn_ctx* ctx);
 int hcnn_set_stream(hcnn_ctx* ctx, void* hip_stream);
 
@@ -162,6 +167,14 @@ int hcnn_encrypt(hcnn_ctx* ctx, const uint32_t* pk_dev, const uint32_t* m_dev, c
  *   sk_dev int32[n]; ct_dev uint32[n_ct][2][k][n]; m_out_dev uint32[n_ct][n]. */
 int hcnn_decrypt(hcnn_ctx* ctx, const int32_t* sk_dev, const uint32_t* ct_dev, size_t n_ct,
                  uint32_t* m_out_dev);
+
+/* The same two operations for a context whose t is 2^32 or more: the plaintext polynomials are
+ * uint64[n_ct][n] with entries in [0,t).  (hcnn_encrypt / hcnn_decrypt return HCNN_ERR_T on such a
+ * context, and these return HCNN_ERR_T on a context with t < 2^32.) */
+int hcnn_encrypt_wide(hcnn_ctx* ctx, const uint32_t* pk_dev, const uint64_t* m_dev, const int32_t* u_dev,
+                      const int32_t* e1_dev, const int32_t* e2_dev, size_t n_ct, uint32_t* ct_out_dev);
+int hcnn_decrypt_wide(hcnn_ctx* ctx, const int32_t* sk_dev, const uint32_t* ct_dev, size_t n_ct,
+                      uint64_t* m_out_dev);
 
 /* Noise read-out (the quantity behind the noise-budget figure of Sec. 5.5): with x = [c0 + c1*s]_q,
  * t*x = q*(m + t*a) + r for the centred remainder r = [t*x]_q; r/q is the invariant noise and Decrypt

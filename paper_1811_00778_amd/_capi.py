@@ -15,8 +15,8 @@ MAX_LIMBS, MAX_FILTERS = 32, 16
 # name -> argtypes; every entry point returns int except hcnn_strerror
 SIGNATURES = {
     "hcnn_gen_primes": [C.c_uint32, C.c_uint32, u32p],
-    "hcnn_min_aux_count": [C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p, C.c_uint32, u32p],
-    "hcnn_ctx_create": [C.POINTER(ptr), C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p, C.c_uint32, ptr],
+    "hcnn_min_aux_count": [C.c_uint32, C.c_uint32, u32p, C.c_uint64, u32p, C.c_uint32, u32p],
+    "hcnn_ctx_create": [C.POINTER(ptr), C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p, C.c_uint64, ptr],
     "hcnn_ctx_destroy": [ptr],
     "hcnn_set_stream": [ptr, ptr],
     "hcnn_set_relin_key": [ptr, ptr],
@@ -28,6 +28,8 @@ SIGNATURES = {
     "hcnn_keygen": [ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr],
     "hcnn_encrypt": [ptr, ptr, ptr, ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_decrypt": [ptr, ptr, ptr, C.c_size_t, ptr],
+    "hcnn_encrypt_wide": [ptr, ptr, ptr, ptr, ptr, ptr, C.c_size_t, ptr],
+    "hcnn_decrypt_wide": [ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_noise_bits": [ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_get_stat": [ptr, C.c_int, u64p],
     "hcnn_reset_stats": [ptr],

@@ -103,21 +103,30 @@ class OpsMixin:
                       self._ptr(pk), self._ptr(evk) if evk is not None else None)
         return pk, evk
 
+    @property
+    def wide_plaintext(self):
+        """True when t needs 64-bit plaintext words (hcnn_encrypt_wide / hcnn_decrypt_wide)."""
+        return self.raw.t >= (1 << 32)
+
     def encrypt(self, pk, m, u, e1, e2):
-        """m [n_ct][n] u32 in [0,t); u, e1, e2 [n_ct][n] i32 -> [n_ct][2][k][n] (hcnn_encrypt)."""
-        for x, d in ((pk, "u32"), (m, "u32"), (u, "i32"), (e1, "i32"), (e2, "i32")):
+        """m [n_ct][n] in [0,t) (u32 words, u64 when t >= 2^32); u, e1, e2 [n_ct][n] i32 -> [n_ct][2][k][n]
+        (hcnn_encrypt / hcnn_encrypt_wide)."""
+        word = "u64" if self.wide_plaintext else "u32"
+        for x, d in ((pk, "u32"), (m, word), (u, "i32"), (e1, "i32"), (e2, "i32")):
             self._check(x, d)
         n_ct = self._count(m, (self.n,))
         out = self._empty((n_ct,) + self.ct_shape, "u32")
-        self.raw.call("hcnn_encrypt", self._ptr(pk), self._ptr(m), self._ptr(u), self._ptr(e1), self._ptr(e2),
-                      n_ct, self._ptr(out))
+        self.raw.call("hcnn_encrypt_wide" if self.wide_plaintext else "hcnn_encrypt", self._ptr(pk), self._ptr(m),
+                      self._ptr(u), self._ptr(e1), self._ptr(e2), n_ct, self._ptr(out))
         return out
 
     def decrypt(self, sk, cts):
+        """-> plaintext polynomials [n_ct][n] (u32 words, u64 when t >= 2^32) (hcnn_decrypt / hcnn_decrypt_wide)."""
         self._check(sk, "i32"); self._check(cts, "u32")
         n_ct = self._count(cts, self.ct_shape)
-        out = self._empty((n_ct, self.n), "u32")
-        self.raw.call("hcnn_decrypt", self._ptr(sk), self._ptr(cts), n_ct, self._ptr(out))
+        out = self._empty((n_ct, self.n), "u64" if self.wide_plaintext else "u32")
+        self.raw.call("hcnn_decrypt_wide" if self.wide_plaintext else "hcnn_decrypt", self._ptr(sk), self._ptr(cts),
+                      n_ct, self._ptr(out))
         return out
 
     def noise_bits(self, sk, cts):

@@ -40,14 +40,15 @@ def choose_moduli(n: int, k: int, t: int):
     return q, rest[:k_aux]
 
 
-_DT = {"u32": torch.int32, "i32": torch.int32}
+_DT = {"u32": torch.int32, "i32": torch.int32, "u64": torch.int64}
 
 
 class Context(OpsMixin):
     """An hcnn_ctx bound to the current torch device and stream.
 
     uint32 residues are carried in torch.int32 tensors (same 32 bits; torch has no
-    arithmetic on uint32, and none is needed here)."""
+    arithmetic on uint32, and none is needed here); the 64-bit plaintext words of a
+    plaintext modulus above 2^32 in torch.int64 tensors."""
 
     def __init__(self, n, q_primes, p_primes, t, device="cuda:0"):
         if not torch.cuda.is_available():
@@ -71,9 +72,9 @@ class Context(OpsMixin):
         return torch.empty(shape, dtype=_DT[dtype_name], device=self.device)
 
     def _check(self, x, dtype_name):
-        if not isinstance(x, torch.Tensor) or x.dtype != torch.int32 or not x.is_contiguous() \
+        if not isinstance(x, torch.Tensor) or x.dtype != _DT[dtype_name] or not x.is_contiguous() \
                 or x.device != self.device:
-            raise TypeError("expected a contiguous int32 tensor on %s" % self.device)
+            raise TypeError("expected a contiguous %s tensor on %s" % (_DT[dtype_name], self.device))
 
     # host <-> device convenience (numpy uint32/int32 arrays)
     def to_device(self, array):
@@ -81,11 +82,14 @@ class Context(OpsMixin):
         a = np.ascontiguousarray(array)
         if a.dtype == np.uint32:
             a = a.view(np.int32)
-        elif a.dtype != np.int32:
-            raise TypeError("uint32 or int32 expected")
+        elif a.dtype == np.uint64:
+            a = a.view(np.int64)            # 64-bit plaintext words of a wide plaintext modulus
+        elif a.dtype not in (np.int32, np.int64):
+            raise TypeError("uint32, int32 or uint64 expected")
         return torch.from_numpy(a).to(self.device)
 
     def to_host_u32(self, tensor):
         import numpy as np
         torch.cuda.current_stream(self.device).synchronize()
-        return tensor.cpu().numpy().view(np.uint32)
+        a = tensor.cpu().numpy()
+        return a.view(np.uint64) if a.dtype == np.int64 else a.view(np.uint32)

@@ -658,6 +658,7 @@ struct AddSmallArgs {
   const uint32_t* x;
   const int32_t* small;        // [count][n]
   const uint32_t* msg;         // [count][n] or null
+  const uint64_t* msg64;       // [count][n] or null: the plaintext in 64-bit words (plaintext modulus above 2^32)
   const ShoupConst* scale;     // [k] (floor(q/t) mod q_l) or null
   uint32_t* out;
   const Mod* mods;
@@ -680,6 +681,7 @@ struct AddSmallKernel {
     const uint32_t sv = small_to_res(a.small[poly * a.n + c], m);
     uint32_t r = a.subtract_small ? sub_mod(a.x[row * a.n + c], sv, m.p) : add_mod(a.x[row * a.n + c], sv, m.p);
     if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
+    if (a.msg64) r = add_mod(r, shoup_mul(reduce64(a.msg64[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
     a.out[(poly * a.out_poly_rows + a.out_row0 + l) * a.n + c] = r;
   }
 };
@@ -761,6 +763,52 @@ struct DecRoundKernel {
     uint64_t acc = ((uint64_t)v * ldc(a.bc.Vp, 0)) % a.t;
     for (uint32_t i = 0; i < ks; ++i) acc = (acc + (uint64_t)zcol[i * kThreads] * ldc(a.bc.Bp, i)) % a.t;
     a.m_out[poly * n + c] = (uint32_t)((acc * a.neg_qinv_t) % a.t);
+  }
+};
+
+// Decrypt rounding for a plaintext modulus of up to 47 bits (64-bit plaintext words).  Same conversion as above
+// with the destination arithmetic done modulo t in 64-bit words: a 32-bit by 47-bit product is formed from
+// two 16-bit halves, each partial product below 2^63.
+struct DecRoundWideArgs {
+  const uint32_t* x;
+  uint64_t* m_out;
+  BConvDev bc;             // source side only (zmul = t*(q/q_i)^-1, xmul = t)
+  const uint64_t* tab;     // [ks + 2]: (q/q_i) mod t for i < ks, then t - (q mod t), then -q^-1 mod t
+  uint64_t t;
+  uint32_t n;
+  uint32_t band;
+  unsigned long long* fallback_counter;
+};
+HCNN_HD uint64_t mul32_mod_wide(uint32_t a, uint64_t b, uint64_t t) {     // a*b mod t for b < t < 2^47
+  uint64_t r = ((uint64_t)(a >> 16) * b) % t;
+  r = (r << 16) % t;
+  return (r + ((uint64_t)(a & 0xffffu) * b) % t) % t;
+}
+HCNN_HD uint64_t mul_mod_wide(uint64_t a, uint64_t b, uint64_t t) {       // a*b mod t for a, b < t < 2^47
+  uint64_t r = mul32_mod_wide((uint32_t)(a >> 32), b, t);                  // a = hi*2^32 + lo
+  r = (r << 16) % t;
+  r = (r << 16) % t;
+  return (r + mul32_mod_wide((uint32_t)a, b, t)) % t;
+}
+struct DecRoundWideKernel {
+  static constexpr int kThreads = kEwThreads;
+  static constexpr int kPhases = 1;
+  struct Regs {};
+  static size_t lds_bytes(uint32_t ks) { return (size_t)2 * ks * kThreads * 4; }
+  template <int PH>
+  HCNN_HD static void phase(const DecRoundWideArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+    const uint32_t ks = a.bc.ks, n = a.n;
+    const uint32_t per_poly = n / kThreads;
+    const size_t poly = bid / per_poly;
+    const uint32_t c = (bid % per_poly) * kThreads + tid;
+    const uint32_t* src = a.x + poly * ks * n + c;
+    uint32_t* zcol = lds + tid;
+    uint32_t* gcol = lds + (size_t)ks * kThreads + tid;
+    auto in = [&](uint32_t i) { return src[(size_t)i * n]; };
+    const uint32_t v = bconv_prepare(a.bc, in, zcol, gcol, kThreads, a.band, a.fallback_counter);
+    uint64_t acc = mul32_mod_wide(v, a.tab[ks], a.t);
+    for (uint32_t i = 0; i < ks; ++i) acc = (acc + mul32_mod_wide(zcol[i * kThreads], a.tab[i], a.t)) % a.t;
+    a.m_out[poly * n + c] = mul_mod_wide(acc, a.tab[ks + 1], a.t);
   }
 };
 

@@ -50,6 +50,46 @@ bool h_is_prime(uint32_t x) {
   return true;
 }
 
+// 64-bit variants for the plaintext modulus (up to 47 bits)
+uint64_t h_mulmod64(uint64_t a, uint64_t b, uint64_t m) { return (uint64_t)((unsigned __int128)a * b % m); }
+uint64_t h_powmod64(uint64_t b, uint64_t e, uint64_t m) {
+  uint64_t r = 1 % m;
+  b %= m;
+  while (e) {
+    if (e & 1) r = h_mulmod64(r, b, m);
+    b = h_mulmod64(b, b, m);
+    e >>= 1;
+  }
+  return r;
+}
+bool h_is_prime64(uint64_t x) {
+  if (x < 2) return false;
+  for (uint64_t sp : {2ull, 3ull, 5ull, 7ull, 11ull, 13ull, 17ull, 19ull, 23ull, 29ull, 31ull, 37ull}) {
+    if (x % sp == 0) return x == sp;
+  }
+  uint64_t d = x - 1;
+  int r = 0;
+  while ((d & 1) == 0) { d >>= 1; ++r; }
+  for (uint64_t a : {2ull, 3ull, 5ull, 7ull, 11ull, 13ull, 17ull, 19ull, 23ull, 29ull, 31ull, 37ull}) {   // decides every x < 2^64
+    uint64_t y = h_powmod64(a, d, x);
+    if (y == 1 || y == x - 1) continue;
+    bool comp = true;
+    for (int i = 1; i < r; ++i) {
+      y = h_mulmod64(y, y, x);
+      if (y == x - 1) { comp = false; break; }
+    }
+    if (comp) return false;
+  }
+  return true;
+}
+// product of all `ms` except index `skip` (skip < 0: all), modulo a 64-bit m
+uint64_t h_prod_mod64(const std::vector<uint32_t>& ms, int skip, uint64_t m) {
+  uint64_t r = 1 % m;
+  for (int i = 0; i < (int)ms.size(); ++i)
+    if (i != skip) r = h_mulmod64(r, ms[i] % m, m);
+  return r;
+}
+
 // psi = x^((p-1)/2n) for the smallest x >= 2 giving order exactly 2n
 uint32_t h_root_of_unity(uint32_t n, uint32_t p) {
   const uint64_t e = ((uint64_t)p - 1) / (2ull * n);
@@ -135,11 +175,25 @@ int check_primes(uint32_t n, const uint32_t* q, uint32_t k, const uint32_t* p, u
 }
 
 // is prod(p[0..kp)) > t*n*prod(q) + 1 ?
-bool aux_sufficient(uint32_t n, const uint32_t* q, uint32_t k, uint32_t t, const uint32_t* p, uint32_t kp) {
+bool aux_sufficient(uint32_t n, const uint32_t* q, uint32_t k, uint64_t t, const uint32_t* p, uint32_t kp) {
   Big lhs{1}, rhs{1};
   for (uint32_t j = 0; j < kp; ++j) big_mul_small(lhs, p[j]);
   for (uint32_t i = 0; i < k; ++i) big_mul_small(rhs, q[i]);
-  big_mul_small(rhs, t);
+  // t < 2^47 = (t >> 24) * 2^24 + (t & 0xffffff): two small factors and a sum
+  {
+    Big hi = rhs;
+    big_mul_small(hi, (uint32_t)(t >> 24));
+    big_mul_small(hi, 1u << 24);
+    big_mul_small(rhs, (uint32_t)(t & 0xffffffu));
+    if (rhs.size() < hi.size()) rhs.resize(hi.size(), 0);
+    uint64_t carry = 0;
+    for (size_t w = 0; w < rhs.size(); ++w) {
+      const uint64_t sum = (uint64_t)rhs[w] + (w < hi.size() ? hi[w] : 0) + carry;
+      rhs[w] = (uint32_t)sum;
+      carry = sum >> 32;
+    }
+    if (carry) rhs.push_back((uint32_t)carry);
+  }
   big_mul_small(rhs, n);
   big_add_small(rhs, 1);
   return big_cmp(lhs, rhs) > 0;
@@ -158,7 +212,8 @@ struct BConvHost {
 };
 
 struct hcnn_ctx {
-  uint32_t n = 0, logn = 0, k = 0, kp = 0, t = 0;
+  uint32_t n = 0, logn = 0, k = 0, kp = 0;
+  uint64_t t = 0;
   std::vector<uint32_t> q, p;
   hcnn_stream_t stream = nullptr;
   std::vector<void*> owned;
@@ -171,6 +226,7 @@ struct hcnn_ctx {
   uint32_t* d_tq_inv = nullptr;     // [kp] t * q^-1 mod p_j
   BConvDev ext{}, to_p{}, to_q{}, dec{};
   uint32_t neg_qinv_t = 0;
+  uint64_t* d_dec_wide = nullptr;   // plaintext modulus above 2^32: [k + 2] constants of the decrypt rounding
   unsigned long long* d_counters = nullptr;   // [2]
 
   uint32_t* d_evk_hat = nullptr;
@@ -269,7 +325,7 @@ int fold_profile(hcnn_ctx* c) {
 //   zfac[i]   extra factor folded into z_i (1 or t), also used as xmul
 //   fold_inv  when true the tables give -(x * M^-1): Bp = m'_j - m_i^-1, Vp = 1
 //             otherwise they give x:                 Bp = M/m_i mod m'_j, Vp = m'_j - M mod m'_j
-BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_t>& dst, uint32_t zfac,
+BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_t>& dst, uint64_t zfac,
                      bool fold_inv, bool dst_is_rns_prime) {
   BConvHost h;
   h.ks = (uint32_t)src.size();
@@ -278,8 +334,8 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
     const uint32_t m = src[i];
     h.src_mod.push_back(h_mod(m));
     const uint32_t Mi_inv = h_inv(h_prod_mod(src, (int)i, m), m);        // (M/m_i)^-1 mod m_i
-    h.zmul.push_back(h_shoup(h_mulmod(Mi_inv, zfac % m, m), m));
-    h.xmul.push_back(h_shoup(zfac % m, m));
+    h.zmul.push_back(h_shoup(h_mulmod(Mi_inv, (uint32_t)(zfac % m), m), m));
+    h.xmul.push_back(h_shoup((uint32_t)(zfac % m), m));
   }
   h.ginv.assign((size_t)h.ks * h.ks, 0);
   for (uint32_t i = 0; i < h.ks; ++i)
@@ -365,21 +421,31 @@ int build_tables(hcnn_ctx* c) {
   if ((e = upload(c, twi, &c->d_tw_inv))) return e;
 
   // floor(q/t) mod q_l = -(q mod t) * t^-1 mod q_l   (q = 0 mod q_l)
-  const uint32_t q_mod_t = h_prod_mod(c->q, -1, c->t);
+  const uint64_t q_mod_t = h_prod_mod64(c->q, -1, c->t);
   std::vector<ShoupConst> delta;
   for (uint32_t l = 0; l < c->k; ++l) {
     const uint32_t ql = c->q[l];
-    const uint32_t v = h_mulmod((ql - q_mod_t % ql) % ql, h_inv(c->t % ql, ql), ql);
+    const uint32_t v = h_mulmod((ql - (uint32_t)(q_mod_t % ql)) % ql, h_inv((uint32_t)(c->t % ql), ql), ql);
     delta.push_back(h_shoup(v, ql));
   }
   if ((e = upload(c, delta, &c->d_delta))) return e;
 
   // decryption: r = [t*x]_q converted to the modulus t
-  {
-    BConvHost h = make_bconv(c->q, std::vector<uint32_t>{c->t}, c->t, false, false);
+  if (c->t < (1ull << 32)) {
+    const uint32_t t32 = (uint32_t)c->t;
+    BConvHost h = make_bconv(c->q, std::vector<uint32_t>{t32}, c->t, false, false);
     if ((e = upload_bconv(c, h, &c->dec))) return e;
-    const uint32_t qinv_t = h_inv(q_mod_t, c->t);
-    c->neg_qinv_t = (c->t - qinv_t) % c->t;
+    const uint32_t qinv_t = h_inv((uint32_t)q_mod_t, t32);
+    c->neg_qinv_t = (t32 - qinv_t) % t32;
+  } else {
+    // source side of the same conversion; the destination constants modulo the wide t live in 64-bit words
+    BConvHost h = make_bconv(c->q, std::vector<uint32_t>{}, c->t, false, false);
+    if ((e = upload_bconv(c, h, &c->dec))) return e;
+    std::vector<uint64_t> tab;
+    for (uint32_t i = 0; i < c->k; ++i) tab.push_back(h_prod_mod64(c->q, (int)i, c->t));
+    tab.push_back((c->t - q_mod_t) % c->t);
+    tab.push_back((c->t - h_powmod64(q_mod_t, c->t - 2, c->t)) % c->t);
+    if ((e = upload(c, tab, &c->d_dec_wide))) return e;
   }
   if (c->kp) {
     BConvHost h_ext = make_bconv(c->q, c->p, 1, false, true);
@@ -391,7 +457,7 @@ int build_tables(hcnn_ctx* c) {
     std::vector<uint32_t> tq;
     for (uint32_t j = 0; j < c->kp; ++j) {
       const uint32_t pj = c->p[j];
-      tq.push_back(h_mulmod(c->t % pj, h_inv(h_prod_mod(c->q, -1, pj), pj), pj));
+      tq.push_back(h_mulmod((uint32_t)(c->t % pj), h_inv(h_prod_mod(c->q, -1, pj), pj), pj));
     }
     if ((e = upload(c, tq, &c->d_tq_inv))) return e;
   }
@@ -475,7 +541,7 @@ int ext_dispatch(hcnn_ctx* c, size_t grid, const ExtArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_EXT_CASE(K, KP) \
   if (k == K && kp == KP) return run<ExtKernelT<K, KP>>(c, grid, ExtKernelT<K, KP>::lds_bytes(), a);
-  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(10, 12) HCNN_EXT_CASE(11, 12) HCNN_EXT_CASE(12, 13) HCNN_EXT_CASE(12, 14) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
+  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(10, 12) HCNN_EXT_CASE(11, 12) HCNN_EXT_CASE(11, 13) HCNN_EXT_CASE(12, 13) HCNN_EXT_CASE(12, 14) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
 #undef HCNN_EXT_CASE
   return run<ExtKernel>(c, grid, ExtKernel::lds_bytes(k), a);
 }
@@ -484,7 +550,7 @@ int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_SCALE_CASE(K, KP) \
   if (k == K && kp == KP) return run<ScaleKernelR<K, KP>>(c, grid, ScaleKernelR<K, KP>::lds_bytes(), a);
-  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(10, 12) HCNN_SCALE_CASE(11, 12) HCNN_SCALE_CASE(12, 13) HCNN_SCALE_CASE(12, 14) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
+  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(10, 12) HCNN_SCALE_CASE(11, 12) HCNN_SCALE_CASE(11, 13) HCNN_SCALE_CASE(12, 13) HCNN_SCALE_CASE(12, 14) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
 #undef HCNN_SCALE_CASE
   return run<ScaleKernel>(c, grid, ScaleKernel::lds_bytes(k, kp), a);
 }
@@ -547,13 +613,14 @@ int hcnn_gen_primes(uint32_t n, uint32_t count, uint32_t* primes_host) {
   return HCNN_OK;
 }
 
-int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q, uint32_t t, const uint32_t* cand,
+int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q, uint64_t t, const uint32_t* cand,
                        uint32_t n_cand, uint32_t* k_aux_out) {
   if (!q || !cand || !k_aux_out) return HCNN_ERR_NULL;
   if (!valid_n(n)) return HCNN_ERR_N;
   if (k == 0 || k > HCNN_MAX_LIMBS || n_cand == 0 || n_cand > 2 * HCNN_MAX_LIMBS) return HCNN_ERR_ARG;
   int e = check_primes(n, q, k, cand, n_cand);
   if (e) return e;
+  if (t < 2 || t >= (1ull << 47)) return HCNN_ERR_T;
   for (uint32_t kp = 1; kp <= n_cand && kp <= HCNN_MAX_LIMBS; ++kp) {
     if (aux_sufficient(n, q, k, t, cand, kp)) {
       *k_aux_out = kp;
@@ -564,14 +631,18 @@ int hcnn_min_aux_count(uint32_t n, uint32_t k, const uint32_t* q, uint32_t t, co
 }
 
 int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, uint32_t k_aux,
-                    const uint32_t* p, uint32_t t, void* hip_stream) {
+                    const uint32_t* p, uint64_t t, void* hip_stream) {
   if (!out || !q || (k_aux && !p)) return HCNN_ERR_NULL;
   *out = nullptr;
   if (!valid_n(n)) return HCNN_ERR_N;
   if (k == 0 || k > HCNN_MAX_LIMBS || k_aux > HCNN_MAX_LIMBS) return HCNN_ERR_ARG;
   int e = check_primes(n, q, k, p, k_aux);
   if (e) return e;
-  if (t < 2 || t >= (1u << 29) || !h_is_prime(t)) return HCNN_ERR_T;
+  if (t < 2 || t >= (1ull << 47) || !h_is_prime64(t)) return HCNN_ERR_T;
+  for (uint32_t i = 0; i < k; ++i)
+    if (q[i] == t) return HCNN_ERR_T;
+  for (uint32_t j = 0; j < k_aux; ++j)
+    if (p[j] == t) return HCNN_ERR_T;
   if (k_aux && !aux_sufficient(n, q, k, t, p, k_aux)) return HCNN_ERR_AUX;
 
   hcnn_ctx* c = new (std::nothrow) hcnn_ctx();
@@ -785,7 +856,7 @@ int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t*
   PointMulArgs pm{tmp, s_hat, tmp, c->d_mods, k, n, k, k, 1u};
   if ((e = run<PointMulKernel>(c, (size_t)k * bpp, 0, pm))) return e;
   if ((e = ntt_dense(c, tmp, tmp, k, k, true))) return e;
-  AddSmallArgs as{tmp, e_small, nullptr, nullptr, pk_out, c->d_mods, k, n, 0u, 2 * k, 0u};
+  AddSmallArgs as{tmp, e_small, nullptr, nullptr, nullptr, pk_out, c->d_mods, k, n, 0u, 2 * k, 0u};
   if ((e = run<AddSmallKernel>(c, (size_t)k * bpp, 0, as))) return e;
   if ((e = copy_d2d(pk_out + poly, a, poly * 4, c->stream))) return e;
   if (!evk_out) return HCNN_OK;
@@ -799,7 +870,7 @@ int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t*
   PointMulArgs pe{tmp, s_hat, tmp, c->d_mods, k, n, k * k, k, 1u};
   if ((e = run<PointMulKernel>(c, (size_t)k * k * bpp, 0, pe))) return e;
   if ((e = ntt_dense(c, tmp, tmp, (size_t)k * k, k, true))) return e;
-  AddSmallArgs ae{tmp, e_evk, nullptr, nullptr, evk_out, c->d_mods, k, n, 1u, 2 * k, 0u};
+  AddSmallArgs ae{tmp, e_evk, nullptr, nullptr, nullptr, evk_out, c->d_mods, k, n, 1u, 2 * k, 0u};
   if ((e = run<AddSmallKernel>(c, (size_t)k * k * bpp, 0, ae))) return e;
   AddDiagArgs ad{evk_out, s2, c->d_mods, k, n};
   if ((e = run<AddDiagKernel>(c, (size_t)k * bpp, 0, ad))) return e;
@@ -808,9 +879,10 @@ int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t*
   return HCNN_OK;
 }
 
-int hcnn_encrypt(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const int32_t* u, const int32_t* e1,
-                 const int32_t* e2, size_t n_ct, uint32_t* ct_out) {
-  if (!c || !pk || !m || !u || !e1 || !e2 || !ct_out) return HCNN_ERR_NULL;
+static int encrypt_impl(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const uint64_t* m64, const int32_t* u,
+                        const int32_t* e1, const int32_t* e2, size_t n_ct, uint32_t* ct_out) {
+  if (!c || !pk || (!m && !m64) || !u || !e1 || !e2 || !ct_out) return HCNN_ERR_NULL;
+  if ((m != nullptr) != (c->t < (1ull << 32))) return HCNN_ERR_T;     // word size of the plaintext follows t
   if (!aligned16(pk) || !aligned16(ct_out)) return HCNN_ERR_ALIGN;
   if (n_ct == 0) return HCNN_OK;
   const uint32_t k = c->k, n = c->n;
@@ -833,7 +905,8 @@ int hcnn_encrypt(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const int32
       PointMulArgs pm{u_hat, pk_hat + b * poly, prod, c->d_mods, k, n, (uint32_t)(cc * k), k, 0u};
       if ((e = run<PointMulKernel>(c, cc * k * bpp, 0, pm))) return e;
       if ((e = ntt_dense(c, prod, prod, cc * k, k, true))) return e;
-      AddSmallArgs as{prod, (b == 0 ? e1 : e2) + c0 * rn, b == 0 ? m + c0 * rn : nullptr,
+      AddSmallArgs as{prod, (b == 0 ? e1 : e2) + c0 * rn, (b == 0 && m) ? m + c0 * rn : nullptr,
+                      (b == 0 && m64) ? m64 + c0 * rn : nullptr,
                       b == 0 ? c->d_delta : nullptr, ct_out + c0 * 2 * poly, c->d_mods, k, n, 0u, 2 * k, b * k};
       if ((e = run<AddSmallKernel>(c, cc * k * bpp, 0, as))) return e;
     }
@@ -841,8 +914,22 @@ int hcnn_encrypt(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const int32
   return HCNN_OK;
 }
 
-int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint32_t* m_out) {
-  if (!c || !sk || !ct || !m_out) return HCNN_ERR_NULL;
+int hcnn_encrypt(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, const int32_t* u, const int32_t* e1,
+                 const int32_t* e2, size_t n_ct, uint32_t* ct_out) {
+  if (!m) return HCNN_ERR_NULL;
+  return encrypt_impl(c, pk, m, nullptr, u, e1, e2, n_ct, ct_out);
+}
+
+int hcnn_encrypt_wide(hcnn_ctx* c, const uint32_t* pk, const uint64_t* m, const int32_t* u, const int32_t* e1,
+                      const int32_t* e2, size_t n_ct, uint32_t* ct_out) {
+  if (!m) return HCNN_ERR_NULL;
+  return encrypt_impl(c, pk, nullptr, m, u, e1, e2, n_ct, ct_out);
+}
+
+static int decrypt_impl(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint32_t* m_out,
+                        uint64_t* m_out64) {
+  if (!c || !sk || !ct || (!m_out && !m_out64)) return HCNN_ERR_NULL;
+  if ((m_out != nullptr) != (c->t < (1ull << 32))) return HCNN_ERR_T;
   if (!aligned16(ct)) return HCNN_ERR_ALIGN;
   if (n_ct == 0) return HCNN_OK;
   const uint32_t k = c->k, n = c->n;
@@ -868,12 +955,29 @@ int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct
     if ((e = ntt_dense(c, x, x, cc * k, k, true))) return e;
     AddRowsArgs ar{cts, x, x, c->d_mods, k, n, 2 * k, 0u};
     if ((e = run<AddRowsKernel>(c, cc * k * bpp, 0, ar))) return e;
-    DecRoundArgs da;
-    da.x = x; da.m_out = m_out + c0 * rn; da.bc = c->dec; da.t = c->t; da.neg_qinv_t = c->neg_qinv_t; da.n = n;
-    da.band = c->band; da.fallback_counter = c->d_counters;
-    if ((e = run<DecRoundKernel>(c, cc * bpp, DecRoundKernel::lds_bytes(k), da))) return e;
+    if (m_out) {
+      DecRoundArgs da;
+      da.x = x; da.m_out = m_out + c0 * rn; da.bc = c->dec; da.t = (uint32_t)c->t; da.neg_qinv_t = c->neg_qinv_t; da.n = n;
+      da.band = c->band; da.fallback_counter = c->d_counters;
+      if ((e = run<DecRoundKernel>(c, cc * bpp, DecRoundKernel::lds_bytes(k), da))) return e;
+    } else {
+      DecRoundWideArgs da;
+      da.x = x; da.m_out = m_out64 + c0 * rn; da.bc = c->dec; da.tab = c->d_dec_wide; da.t = c->t; da.n = n;
+      da.band = c->band; da.fallback_counter = c->d_counters;
+      if ((e = run<DecRoundWideKernel>(c, cc * bpp, DecRoundWideKernel::lds_bytes(k), da))) return e;
+    }
   }
   return HCNN_OK;
+}
+
+int hcnn_decrypt(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint32_t* m_out) {
+  if (!m_out) return HCNN_ERR_NULL;
+  return decrypt_impl(c, sk, ct, n_ct, m_out, nullptr);
+}
+
+int hcnn_decrypt_wide(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint64_t* m_out) {
+  if (!m_out) return HCNN_ERR_NULL;
+  return decrypt_impl(c, sk, ct, n_ct, nullptr, m_out);
 }
 
 int hcnn_noise_bits(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n_ct, uint32_t* bits_out) {
@@ -972,7 +1076,7 @@ const char* hcnn_strerror(int code) {
     case HCNN_ERR_NULL: return "null pointer";
     case HCNN_ERR_N: return "n must be a power of two in [1024, 32768]";
     case HCNN_ERR_PRIME: return "modulus is not a distinct prime in (2^29, 2^30) congruent to 1 mod 2n";
-    case HCNN_ERR_T: return "t must be a prime below 2^29";
+    case HCNN_ERR_T: return "t must be a prime below 2^47 other than the ciphertext primes (and the plaintext word size must match it)";
     case HCNN_ERR_AUX: return "auxiliary basis missing or too small (need prod p > t*n*q + 1)";
     case HCNN_ERR_ARG: return "invalid count, size or option";
     case HCNN_ERR_NOKEY: return "relinearisation key not set";

@@ -49,11 +49,13 @@ class EmuContext(OpsMixin):
     def _ptr(self, x):
         return ctypes.c_void_p(x.ctypes.data)
 
+    _NP = {"u32": np.uint32, "i32": np.int32, "u64": np.uint64}
+
     def _empty(self, shape, dtype_name):
-        return np.empty(shape, dtype=np.uint32 if dtype_name == "u32" else np.int32)
+        return np.empty(shape, dtype=self._NP[dtype_name])
 
     def _check(self, x, dtype_name):
-        want = np.uint32 if dtype_name == "u32" else np.int32
+        want = self._NP[dtype_name]
         if not isinstance(x, np.ndarray) or x.dtype != want or not x.flags["C_CONTIGUOUS"]:
             raise TypeError("expected contiguous %s ndarray" % want.__name__)
         if x.ctypes.data % 16:

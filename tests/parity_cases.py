@@ -368,3 +368,53 @@ def check_noise_bits(backend, n, k, seed_id=1):
     assert np.array_equal(got, want), (got, want)
     assert want[7] == 0 and want[4] > want[0] and want[5] > want[4], want   # zero; sum noisier than fresh; square noisier
     s.ctx.close()
+
+
+WIDE_T = 5522259017729          # the 43-bit plaintext modulus of the MNIST parameter sets (parameter table, Sec. 4.2)
+
+
+def check_wide_plaintext(backend, n=1024, k=5, seed_id=1, force_exact=False):
+    """A plaintext modulus above 2^32 (64-bit plaintext words): encrypt, decrypt, squaring with
+    relinearisation and the noise read-out against the oracle, residue by residue and word by word."""
+    t = WIDE_T
+    s = Setup(backend, n, k, t=t, seed_id=seed_id, stream=51)
+    assert len(s.p) == k + 2                                     # t*n has more than 30 bits
+    ctx = s.ctx
+    if force_exact:
+        ctx.set_ambiguity_band(1 << 26)
+    ctx.set_relin_key(backend.dev(s.evk))
+    count = 3
+    polys = s.rng.integers(0, t, size=(count, n), dtype=np.int64).astype(np.uint64)
+    er = gen.encryption_randomness(s.rng, n, count)
+    cts = np.stack([fv.encrypt(s.octx, s.pk, [int(v) for v in polys[i]], er["u"][i], er["e1"][i], er["e2"][i])
+                    for i in range(count)])
+    gcts = ctx.encrypt(backend.dev(s.pk), backend.dev(polys), backend.dev(er["u"]), backend.dev(er["e1"]),
+                       backend.dev(er["e2"]))
+    assert np.array_equal(backend.host(gcts), cts), "wide encrypt"
+    dec = backend.host(ctx.decrypt(backend.dev(s.kr["s"]), gcts))
+    assert dec.dtype == np.uint64 and np.array_equal(dec, polys), "wide decrypt(encrypt)"
+    sq = backend.host(ctx.ct_square_relin(gcts))
+    want = np.stack([fv.square_relin(s.octx, cts[i], s.evk) for i in range(count)])
+    assert np.array_equal(sq, want), "wide squaring"
+    dsq = backend.host(ctx.decrypt(backend.dev(s.kr["s"]), backend.dev(sq)))
+    assert np.array_equal(dsq, np.stack([fv.decrypt(s.octx, s.kr["s"], want[i]) for i in range(count)])), "wide decrypt"
+    picks = [0, 3, n - 1]
+    before = fv.slot_eval(polys, n, t, picks)
+    after = fv.slot_eval(dsq, n, t, picks)
+    for i in range(count):
+        for c in range(len(picks)):
+            assert int(after[i, c]) == int(before[i, c]) ** 2 % t, ("slot squares", i, c)
+    rnd = gen.uniform_residues(s.rng, s.q, n, lead=(2, 2))
+    got = backend.host(ctx.decrypt(backend.dev(s.kr["s"]), backend.dev(rnd)))
+    assert np.array_equal(got, np.stack([fv.decrypt(s.octx, s.kr["s"], rnd[i]) for i in range(2)])), "wide decrypt random"
+    batch = np.concatenate([cts[:1], sq[:1], rnd[:1]])
+    bits = backend.host(ctx.noise_bits(backend.dev(s.kr["s"]), backend.dev(batch)))
+    assert [int(b) for b in bits] == [fv.noise_bits(s.octx, s.kr["s"], batch[i]) for i in range(3)], "wide noise"
+    # the 32-bit entry points refuse a wide context
+    try:
+        ctx.raw.call("hcnn_decrypt", ctx._ptr(backend.dev(s.kr["s"])), ctx._ptr(gcts), 1,
+                     ctx._ptr(backend.dev(np.zeros((1, n), dtype=np.uint32))))
+        raise AssertionError("hcnn_decrypt accepted a wide plaintext modulus")
+    except _capi.HcnnError as exc:
+        assert exc.code == _capi.ERR["T"]
+    ctx.close()

@@ -80,6 +80,11 @@ def test_ctx_create_rejects_bad_arguments(lib):
     assert create(2048, q, p, t) in (E["PRIME"], E["OK"], E["NODEVICE"])  # 1 mod 2048 need not hold
     assert create(n, q, p, 65536) == E["T"]
     assert create(n, q, p, 1) == E["T"]
+    assert create(n, q, p, q[0]) == E["T"]                             # t among the ciphertext primes
+    assert create(n, q, p, p[0]) == E["T"]                             # ... or the auxiliary primes
+    assert create(n, q, p, (1 << 47) + 5) == E["T"]                    # too wide (2^47 + 5 is prime)
+    assert create(n, q, p, 5522259017729 + 2) == E["T"]                # wide and composite
+    assert create(n, q, p, 5522259017729) in (E["AUX"], E["OK"], E["NODEVICE"])   # the 43-bit modulus needs a larger k'
     assert create(n, q, p[:2], t) == E["AUX"]                          # k' = 2 is too small here
     assert lib.hcnn_ctx_create(None, n, 2, _capi.u32_array(q), 0, None, t, None) == E["NULL"]
     h = ctypes.c_void_p()

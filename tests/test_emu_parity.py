@@ -96,6 +96,11 @@ def test_noise_read_out(backend):
     pc.check_noise_bits(backend, 1024, 5)
 
 
+def test_wide_plaintext_modulus(backend):
+    pc.check_wide_plaintext(backend)
+    pc.check_wide_plaintext(backend, 1024, 5, seed_id=2, force_exact=True)
+
+
 def test_plaintext_crt_channels(backend):
     pc.check_crt_channels(backend)
 

@@ -80,6 +80,49 @@ def test_mnist_network_end_to_end():
     ctx.close()
 
 
+def test_mnist_network_paper_parameter_set():
+    """The MNIST-shaped network at parameter set 1 of Sec. 4.2 as printed: N = 2^13, a 330-bit q (eleven 30-bit
+    primes) and the 43-bit plaintext modulus 5522259017729, i.e. a single plaintext channel with 64-bit plaintext
+    words.  Outputs decrypted by the oracle, compared with the plain network on sampled slots."""
+    import torch
+    from test_gpu_parity import GpuBackend
+    from paper_1811_00778_amd import network
+    backend = GpuBackend()
+    n, k, t = 8192, 11, pc.WIDE_T
+    s = pc.Setup(backend, n, k, t=t, seed_id=3, stream=13, with_keys=False)
+    ctx, dev = s.ctx, backend.dev
+    rng = s.rng
+    kr = gen.key_randomness(rng, s.q, n)
+    pk, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
+    ctx.set_relin_key(evk)
+    say("parameter set 1: k=%d, k'=%d, t=%d; GPU encryption of 784 ciphertexts from 64-bit plaintext words" % (k, len(s.p), t))
+    polys = rng.integers(0, t, size=(784, n), dtype=np.int64).astype(np.uint64)
+    er = gen.encryption_randomness(rng, n, 784)
+    cts = ctx.encrypt(pk, dev(polys), dev(er["u"]), dev(er["e1"]), dev(er["e2"]))
+    weights = _weights(rng, network.MNIST_HCNN, network.MNIST_INPUT, 15)
+    plan = network.Plan(network.MNIST_HCNN, network.MNIST_INPUT, weights, dev)
+    plan.run(ctx, cts)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    out = plan.run(ctx, cts)
+    torch.cuda.synchronize()
+    say("encrypted network: %.1f ms on the GPU" % ((time.time() - t0) * 1e3))
+    bits = backend.host(ctx.noise_bits(dev(kr["s"]), out))
+    say("noise budget left in the outputs: %.1f bits" % fv.noise_budget_bits(s.octx, int(bits.max())))
+    host_out = backend.host(out)
+    picks = [0, 4097, n - 1]
+    say("plain evaluation mod t on %d sampled slots (Python integers)" % len(picks))
+    x = fv.slot_eval(polys, n, t, picks).reshape(1, 28, 28, len(picks))
+    want = plain_net.evaluate(network.MNIST_HCNN, weights, x, t).reshape(10, len(picks))
+    gpu_dec = backend.host(ctx.decrypt(dev(kr["s"]), out))
+    for o in range(10):
+        m = fv.decrypt(s.octx, kr["s"], host_out[o])
+        assert np.array_equal(m, gpu_dec[o]), ("GPU decryption", o)
+        got = fv.slot_eval(m[None, :], n, t, picks)[0]
+        assert [int(v) for v in got] == [int(v) for v in want[o]], ("network output", o)
+    ctx.close()
+
+
 def test_cifar10_network_full_width_end_to_end():
     import torch
     from test_gpu_parity import GpuBackend

@@ -148,6 +148,12 @@ def test_noise_read_out(backend):
     pc.check_noise_bits(backend, 8192, 8, seed_id=2)
 
 
+def test_wide_plaintext_modulus(backend):
+    say("43-bit plaintext modulus: n=1024 k=5, n=4096 k=6 with the exact rounding path forced")
+    pc.check_wide_plaintext(backend)
+    pc.check_wide_plaintext(backend, 4096, 6, seed_id=2, force_exact=True)
+
+
 def test_plaintext_crt_channels(backend):
     say("two plaintext moduli of the CIFAR-10 parameter set as CRT channels")
     pc.check_crt_channels(backend)
