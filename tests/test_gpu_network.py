@@ -171,3 +171,73 @@ def test_cifar10_network_full_width_end_to_end():
         got = fv.slot_eval(m[None, :], n, t, picks)[0]
         assert np.array_equal(got, want[o]), ("network output", o, got, want[o])
     ctx.close()
+
+
+def test_cifar10_network_ten_crt_channels():
+    """The CIFAR-10-shaped network as the paper deploys it (Sec. 3.1.2, parameter set 5): ten independent plaintext
+    channels, one per modulus of the parameter table, whose decrypted outputs are recombined by the CRT map into the
+    integers the network produces over Z (up to ~180 bits here, far beyond any single modulus).  Every input
+    ciphertext encrypts a constant polynomial (the pixel value in every slot), so the same integers enter every
+    channel without slot encoding; the expected integers come from the plain network evaluated in Python integers."""
+    import os
+    import torch
+    from test_gpu_parity import GpuBackend
+    from paper_1811_00778_amd import network
+    path = os.path.join(os.path.dirname(__file__), "golden", "cifar_plaintext_moduli.txt")
+    moduli = [int(l) for l in open(path) if l.strip() and l[0] != "#"]
+    free, _total = torch.cuda.mem_get_info()
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs about 50 GiB of device memory")
+    backend = GpuBackend()
+    n, k = 8192, 10
+    spec, in_shape = network.CIFAR10_HCNN, network.CIFAR10_INPUT
+    n_in = in_shape[0] * in_shape[1] * in_shape[2]
+    rng = gen.rng_for(4, 14)
+    pixels = rng.integers(0, 16, size=n_in).astype(np.int64)
+    weights = _weights(rng, spec, in_shape, 3)
+    big = 1
+    for t in moduli:
+        big *= t
+    say("plain network over the integers")
+    true = plain_net.evaluate(spec, weights, pixels.reshape(in_shape + (1,)), big).reshape(10)
+    true = [int(v) if int(v) <= big // 2 else int(v) - big for v in true]           # centred representatives
+    assert max(abs(v) for v in true) > max(moduli) ** 4 and 2 * max(abs(v) for v in true) < big
+    kr = None
+    er = gen.encryption_randomness(rng, n, 256)            # reused for every block of 256 inputs and every channel
+    residues = []
+    total = 0.0
+    for ch, t in enumerate(moduli):
+        s = pc.Setup(backend, n, k, t=t, seed_id=4, stream=15, with_keys=False)
+        ctx, dev = s.ctx, backend.dev
+        if kr is None:
+            kr = gen.key_randomness(rng, s.q, n)
+        pk, evk = ctx.keygen(dev(kr["s"]), dev(kr["a"]), dev(kr["e"]), dev(kr["a_evk"]), dev(kr["e_evk"]))
+        ctx.set_relin_key(evk)
+        polys = np.zeros((n_in, n), dtype=np.uint32)
+        polys[:, 0] = pixels % t
+        cts = torch.empty((n_in, 2, k, n), dtype=torch.int32, device="cuda")
+        d_er = {name: dev(v) for name, v in er.items()}
+        for i0 in range(0, n_in, 256):
+            cts[i0:i0 + 256] = ctx.encrypt(pk, dev(polys[i0:i0 + 256]), d_er["u"], d_er["e1"], d_er["e2"])
+        plan = network.Plan(spec, in_shape, weights, dev)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        out = plan.run(ctx, cts)
+        torch.cuda.synchronize()
+        total += time.time() - t0
+        host_out = backend.host(out)
+        dec = backend.host(ctx.decrypt(dev(kr["s"]), out))
+        del out, cts, plan
+        torch.cuda.empty_cache()
+        want0 = fv.decrypt(s.octx, kr["s"], host_out[0])                            # one oracle decryption per channel
+        assert np.array_equal(dec[0], want0), ("GPU decryption", t)
+        assert not dec[:, 1:].any(), ("outputs are constant polynomials", t)
+        assert [int(v) for v in dec[:, 0]] == [v % t for v in true], ("channel", t)
+        residues.append([int(v) for v in dec[:, 0]])
+        say("channel %2d, t = %7d: network evaluated and decrypted" % (ch, t))
+        ctx.close()
+    say("ten channels: %.2f s on the GPU in total (each a cold run: first launches, scratch and feature-map allocation)" % total)
+    for o in range(10):
+        v = fv.crt_reconstruct([residues[ch][o] for ch in range(10)], moduli)
+        v = v if v <= big // 2 else v - big
+        assert v == true[o], ("recombined output", o)
