@@ -30,7 +30,7 @@ def backend():
 
 
 @pytest.mark.parametrize("n,k,n_polys,rows", [(1024, 2, 3, None), (2048, 3, 2, 3), (4096, 2, 1, 2),
-                                             (8192, 2, 1, 1), (16384, 1, 1, 1), (32768, 1, 1, 1)])
+                                             (8192, 2, 1, 1), (16384, 1, 1, 1), (32768, 1, 10, 1)])
 def test_ntt_all_sizes(backend, n, k, n_polys, rows):
     pc.check_ntt(backend, n, k, n_polys, rows)
 

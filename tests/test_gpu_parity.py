@@ -42,7 +42,7 @@ def backend():
 
 
 @pytest.mark.parametrize("n,k,n_polys,rows", [(1024, 2, 16, None), (2048, 3, 5, 4), (4096, 2, 3, 2),
-                                             (8192, 8, 7, 3), (16384, 3, 2, 2), (32768, 2, 2, 1)])
+                                             (8192, 8, 7, 3), (16384, 3, 2, 2), (32768, 2, 160, 2)])
 def test_ntt_all_sizes(backend, n, k, n_polys, rows):
     say("ntt n=%d k=%d polys=%d" % (n, k, n_polys))
     pc.check_ntt(backend, n, k, n_polys, rows)
