@@ -141,6 +141,39 @@ def test_hot_path_under_graph_capture(backend):
     ctx.close()
 
 
+def test_two_contexts_on_two_streams(backend):
+    """Two contexts (two plaintext channels) bound to two HIP streams of default priority work at the same time,
+    each with its own scratch memory; both must produce what they produce alone."""
+    import torch
+    say("two contexts on two streams")
+    n, k = 4096, 4
+    setups = [pc.Setup(backend, n, k, t=t, seed_id=2, stream=61 + i) for i, t in enumerate((65537, 2424833))]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    cts, alone = [], []
+    for s in setups:
+        backend._ctx = s.ctx
+        s.ctx.set_relin_key(backend.dev(s.evk))
+        x = backend.dev(gen.uniform_residues(s.rng, s.q, n, lead=(48, 2)))
+        cts.append(x)
+        alone.append(s.ctx.ct_square_relin(x).clone())
+    torch.cuda.synchronize()
+    outs = [torch.zeros_like(a) for a in alone]
+    for rep in range(3):
+        for s, st, x, o in zip(setups, streams, cts, outs):
+            with torch.cuda.stream(st):
+                s.ctx.use_stream(st)
+                s.ctx.ct_square_relin(x, out=o)
+        torch.cuda.synchronize()
+        for o, a in zip(outs, alone):
+            assert torch.equal(o, a), ("concurrent run", rep)
+            o.zero_()
+    want = fv.square_relin(setups[1].octx, backend.host(cts[1])[5], setups[1].evk)
+    assert np.array_equal(backend.host(alone[1])[5], want)
+    for s in setups:
+        s.ctx.use_stream()
+        s.ctx.close()
+
+
 def test_noise_read_out(backend):
     say("noise read-out n=1024 k=2, n=2048 k=5, n=8192 k=8")
     pc.check_noise_bits(backend, 1024, 2)
