@@ -296,9 +296,27 @@ def main():
             butterflies = (n // 2) * (n.bit_length() - 1)
             instr_per_launch = rows_per_launch * butterflies * 8
             ach = instr_per_launch / avg_s / 1e12
-            bytes_per_launch = rows_per_launch * row_bytes
+            # Algorithmic HBM bytes of the class's three launches per step (a plain row is read and written once;
+            # the k transforms of a digit row share one read, the three tensor components of a (ciphertext, limb)
+            # pair share two reads, an adding store reads its addend too), and the bytes that the HBM counters
+            # attribute to them: ratios of counted to algorithmic bytes per kernel, measured with rocprofv3
+            # FETCH_SIZE / WRITE_SIZE on this workload (profiles/bench_primitive8192_hbm_counters.md).
+            L_ = k + len(p)
+            row4 = 4 * n
+            if dom == "ntt_fwd":
+                parts = [((ntt_buf.numel() // n + n_ct * 2 * L_) * 2 * row4, 1.078),       # plain rows
+                         (n_ct * k * k * row4 + n_ct * k * row4, 1.030)]                    # digit-reducing load
+            else:
+                parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
+                         (n_ct * 3 * L_ * row4 + n_ct * 2 * L_ * row4, 1.130),              # tensor-forming load
+                         (n_ct * 2 * k * 3 * row4, 1.008)]                                  # adding store
+            per_step_launches = 3
+            bytes_per_launch = sum(b for b, _ in parts) / per_step_launches
+            traffic = sum(b * r for b, r in parts) / per_step_launches
             roofline = dict(kernel=dom, bound="alu", achieved=round(ach, 2), peak=ALU_PEAK_TOPS,
-                            unit="T int32 lane-instr/s", frac=round(ach / ALU_PEAK_TOPS, 4), traffic=None,
+                            unit="T int32 lane-instr/s", frac=round(ach / ALU_PEAK_TOPS, 4), traffic=int(traffic),
+                            traffic_unit="HBM bytes per launch (counter ratios from profiles/bench_primitive8192_hbm_counters.md "
+                                         "applied to the algorithmic bytes)",
                             algorithmic_instr_per_launch=int(instr_per_launch),
                             algorithmic_bytes_per_launch=int(bytes_per_launch),
                             hbm_GBps=round(bytes_per_launch / avg_s / 1e9, 1),
