@@ -51,6 +51,14 @@ HCNN_HD uint32_t reduce64(uint64_t x, const Mod& m) {
   return csub(s, m.p);
 }
 
+// x mod p up to one extra p: result in [0, 2p) for any x < 2^64.
+HCNN_HD uint32_t reduce64_2p(uint64_t x, const Mod& m) {
+  uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
+  uint32_t y = shoup_lazy(hi, m.c32, m.c32s, m.p);
+  uint32_t qb = mulhi32(lo, m.mu) >> 29;
+  return csub(y + (lo - qb * m.p), 2 * m.p);
+}
+
 // x mod p up to three extra p: result in [0, 4p) for any x < 2^64.
 HCNN_HD uint32_t reduce64_lazy(uint64_t x, const Mod& m) {
   uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;

@@ -32,8 +32,8 @@ struct NttLimb {
 // Fused input / output stages (template parameter IO of the kernels):
 //   kNttPlain       rows are read and written as they are
 //   kNttLoadDigit   forward only: row (ct, i, j) reads digit i of y2, i.e. row (ct*3+2)*k + i of `in`
-//                   = y[n_ct][3][k][n], reduced modulo q_j (one conditional subtraction: every prime
-//                   lies in (2^29, 2^30)); output rows dense [ct][i][j]
+//                   = y[n_ct][3][k][n], taken as it is (every prime lies in (2^29, 2^30), so a digit is below
+//                   2*q_j, which the lazy butterflies accept); output rows dense [ct][i][j]
 //   kNttLoadTensor  inverse only: row (ct, b, l) reads c0^ = in[(ct*2)*L + l], c1^ = in[(ct*2+1)*L + l]
 //                   and transforms c0^*c0^, 2*c0^*c1^ or c1^*c1^ for b = 0, 1, 2 (HMult step 1, c = c')
 //   kNttLoadTensorMul  inverse only: the general tensor of HMult step 1 for two different operands;
@@ -140,10 +140,8 @@ struct NttFwd {
 #pragma unroll
       for (int e = 0; e < NET; ++e)
         v[e] = kFirst ? gin[base + (uint32_t)e * TLAST] : lds[lds_elem<LOG_TLAST>(sbase, e)];
-      if constexpr (kFirst && IO == kNttLoadDigit) {
-#pragma unroll
-        for (int e = 0; e < NET; ++e) v[e] = csub(v[e], p);
-      }
+      // (kNttLoadDigit: a digit lies in [0, q_i) and every prime in (2^29, 2^30), so it is below 2p for this
+      // row's prime p: a valid lazily reduced input of the butterflies as it stands)
       const uint32_t root = (1u << S0) + i;
 #pragma unroll
       for (int l = 0; l < NS; ++l) {
@@ -274,9 +272,11 @@ struct NttInv {
             // gin was pointed at c0^ (b = 0, 1) or c1^ (b = 2); only b = 1 needs the second row
             U4 y = t;
             if (comp == 1) y = reinterpret_cast<const U4*>(gin2 + base)[e / 4];
-            t.x = mul_mod(t.x, y.x, L.m); t.y = mul_mod(t.y, y.y, L.m);
-            t.z = mul_mod(t.z, y.z, L.m); t.w = mul_mod(t.w, y.w, L.m);
-            if (comp == 1) { t.x = csub(2 * t.x, p); t.y = csub(2 * t.y, p); t.z = csub(2 * t.z, p); t.w = csub(2 * t.w, p); }
+            // products and the doubled cross term stay lazily reduced in [0, 2p), which is what the first
+            // butterflies of the inverse transform take
+            t.x = reduce64_2p((uint64_t)t.x * y.x, L.m); t.y = reduce64_2p((uint64_t)t.y * y.y, L.m);
+            t.z = reduce64_2p((uint64_t)t.z * y.z, L.m); t.w = reduce64_2p((uint64_t)t.w * y.w, L.m);
+            if (comp == 1) { t.x = csub(2 * t.x, two_p); t.y = csub(2 * t.y, two_p); t.z = csub(2 * t.z, two_p); t.w = csub(2 * t.w, two_p); }
           }
           v[e + 0] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
         }
@@ -293,8 +293,8 @@ struct NttInv {
             }
             if constexpr (IO == kNttLoadTensor) {
               const uint32_t u = comp == 1 ? gin2[base + (uint32_t)e * TLAST] : t;
-              t = mul_mod(t, u, L.m);
-              if (comp == 1) t = csub(2 * t, p);
+              t = reduce64_2p((uint64_t)t * u, L.m);
+              if (comp == 1) t = csub(2 * t, two_p);
             }
             v[e] = t;
           } else {
