@@ -111,7 +111,7 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
   return bconv_round(S, band, exact, fallback_counter);
 }
 
-// Residue of the converted integer modulo destination j; `extra` (< 2^60) is added before reducing.
+// Residue of the converted integer modulo destination j; `extra` (< 2^61) is added before reducing.
 HCNN_HD uint32_t bconv_output(const BConvDev& bc, const uint32_t* zcol, int stride, uint32_t v, uint32_t j,
                               uint64_t extra = 0) {
   const Mod dm = ldc(bc.dst_mod, j);

@@ -513,6 +513,7 @@ int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse, int io) {
   }
   if (io == kNttLoadDigit)
     return run<NttFwd<LOGN, LOGR, kNttLoadDigit>>(c, ntt_grouped_grid(r.rows, r.cycle), lds, a, r.rows);
+  if (io == kNttStoreLazy) return run<NttFwd<LOGN, LOGR, kNttStoreLazy>>(c, r.rows, lds, a);
   return run<NttFwd<LOGN, LOGR>>(c, r.rows, lds, a);
 }
 
@@ -791,11 +792,11 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-    if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false))) return e;
+    if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false, kNttStoreLazy))) return e;
     if (in_b) {
       ea.in = in_b + c0 * ct_words; ea.out = ext_b;
       if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-      if ((e = ntt_dense(c, ext_b, ext_b, cc * 2 * L, L, false))) return e;
+      if ((e = ntt_dense(c, ext_b, ext_b, cc * 2 * L, L, false, kNttStoreLazy))) return e;
     }
     // 3+4. tensor formed while loading, then back to coefficients: the integer tensor, known mod q*p
     if (in_b) {

@@ -40,7 +40,12 @@ struct NttLimb {
 //                   `in` holds the first, `aux` the second (same [ct][2][L][n] layout):
 //                   c0^*c0'^, c0^*c1'^ + c1^*c0'^, c1^*c1'^
 //   kNttStoreAdd    inverse only: row (ct, b, j) adds aux row (ct*3+b)*k + j (aux = y) on the way out
-enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4 };
+//   kNttStoreLazy   forward only: the output is left lazily reduced in [0, 4p) (for rows whose only reader is
+//                   the tensor-forming load, which reduces 64-bit products of any 32-bit operands)
+// The tensor-forming loads also leave their output lazily reduced, in [0, 2p): its only reader multiplies it
+// by a constant with Shoup's method, which takes any 32-bit operand.
+enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4,
+             kNttStoreLazy = 5 };
 
 struct NttArgs {
   const uint32_t* in;
@@ -100,7 +105,7 @@ struct NttGeom {
 // ------------------------------------------------------------------------- forward
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttFwd {
-  static_assert(IO == kNttPlain || IO == kNttLoadDigit, "forward NTT: plain or digit load");
+  static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy, "forward NTT: plain, digit load or lazy store");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
@@ -165,16 +170,20 @@ struct NttFwd {
 #pragma unroll
         for (int e = 0; e < NET; e += 4) {
           U4 t;
-          t.x = csub(csub(v[e + 0], two_p), p);
-          t.y = csub(csub(v[e + 1], two_p), p);
-          t.z = csub(csub(v[e + 2], two_p), p);
-          t.w = csub(csub(v[e + 3], two_p), p);
+          if constexpr (IO == kNttStoreLazy) {
+            t.x = v[e + 0]; t.y = v[e + 1]; t.z = v[e + 2]; t.w = v[e + 3];
+          } else {
+            t.x = csub(csub(v[e + 0], two_p), p);
+            t.y = csub(csub(v[e + 1], two_p), p);
+            t.z = csub(csub(v[e + 2], two_p), p);
+            t.w = csub(csub(v[e + 3], two_p), p);
+          }
           g4[e / 4] = t;
         }
       } else {
 #pragma unroll
         for (int e = 0; e < NET; ++e) {
-          if (kLast) gout[base + (uint32_t)e * TLAST] = csub(csub(v[e], two_p), p);
+          if (kLast) gout[base + (uint32_t)e * TLAST] = IO == kNttStoreLazy ? v[e] : csub(csub(v[e], two_p), p);
           else       lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
         }
       }
@@ -329,8 +338,9 @@ struct NttInv {
 #pragma unroll
         for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = add_mod(csub(v[e], p), addend[e], p);
       } else if constexpr (kLast) {
+        constexpr bool kLazyOut = IO == kNttLoadTensor || IO == kNttLoadTensorMul;
 #pragma unroll
-        for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = csub(v[e], p);
+        for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = kLazyOut ? v[e] : csub(v[e], p);
       } else {
 #pragma unroll
         for (int e = 0; e < NET; ++e) lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
