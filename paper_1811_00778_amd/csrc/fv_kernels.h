@@ -345,9 +345,15 @@ struct RelinMacArgs {
   uint32_t* acc;         // [n_ct][2][k][n]
   const Mod* mods;
   uint32_t k, n;
-  uint32_t n_ct;         // ciphertexts in this launch
+  uint32_t n_grp;        // groups of CT ciphertexts in this launch
+  uint32_t ct_base;      // first ciphertext of the launch
   uint32_t key_major;    // workgroup order, see the kernel
 };
+// A workgroup takes one (limb j, coefficient tile) for CT consecutive ciphertexts: every evaluation-key tile
+// is loaded once and multiplied with the digits of all CT ciphertexts from registers.  (The key is read from
+// L2; with one ciphertext per workgroup it makes up two thirds of what flows from L2 into the compute units,
+// and that flow, not HBM, then bounds the kernel.)
+template <int CT>
 struct RelinMacKernel {
   static constexpr int kThreads = kEwThreads;
   static constexpr int kPhases = 1;
@@ -355,48 +361,65 @@ struct RelinMacKernel {
   template <int PH>
   HCNN_HD static void phase(const RelinMacArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
     const uint32_t per_row = a.n / (kThreads * kEwVec);
-    size_t ct;
+    size_t grp;
     uint32_t j, tile;
     if (a.key_major) {
       // (chosen by the host when the evaluation key outgrows an L2 in the plain order)
       // die x takes the coefficient tiles x, x+8, ... ; for one (limb, tile) it sweeps the ciphertexts of
       // the batch back to back, so the 2k evaluation-key tiles they all multiply with stay in that die's L2
       const uint32_t xcd = bid % kXcds, local = bid / kXcds;
-      ct = local % a.n_ct;
-      const uint32_t rest = local / a.n_ct;
+      grp = local % a.n_grp;
+      const uint32_t rest = local / a.n_grp;
       tile = (rest % (per_row / kXcds)) * kXcds + xcd;
       j = rest / (per_row / kXcds);
     } else {
-      const size_t row = bid / per_row;                     // (ct, j)
+      const size_t row = bid / per_row;                     // (group, j)
       tile = bid % per_row;
-      ct = row / a.k;
+      grp = row / a.k;
       j = (uint32_t)(row % a.k);
     }
+    const size_t ct0 = a.ct_base + grp * CT;
     const uint32_t c = (tile * kThreads + tid) * kEwVec;
     const Mod m = ldc(a.mods, j);
     const size_t rn = a.n;
-    uint64_t s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
+    uint64_t s0[CT][4], s1[CT][4];
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+      for (int q = 0; q < 4; ++q) { s0[t][q] = 0; s1[t][q] = 0; }
     // 15 products below 2^60 (+ a residue) fit 64 bits; inside a run of 15 the loop is unrolled so that the
     // loads of several digits are in flight together
     for (uint32_t i0 = 0; i0 < a.k; i0 += 15) {
       const uint32_t i1 = i0 + 15 < a.k ? i0 + 15 : a.k;
-#pragma unroll 4
+#pragma unroll 2
       for (uint32_t i = i0; i < i1; ++i) {
-        const U4 d = *reinterpret_cast<const U4*>(a.dig + ((ct * a.k + i) * a.k + j) * rn + c);
         const U4 e0 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 0) * a.k + j) * rn + c);
         const U4 e1 = *reinterpret_cast<const U4*>(a.evk + (((size_t)i * 2 + 1) * a.k + j) * rn + c);
-        s0[0] += (uint64_t)d.x * e0.x; s0[1] += (uint64_t)d.y * e0.y; s0[2] += (uint64_t)d.z * e0.z; s0[3] += (uint64_t)d.w * e0.w;
-        s1[0] += (uint64_t)d.x * e1.x; s1[1] += (uint64_t)d.y * e1.y; s1[2] += (uint64_t)d.z * e1.z; s1[3] += (uint64_t)d.w * e1.w;
+        U4 d[CT];
+#pragma unroll
+        for (int t = 0; t < CT; ++t)
+          d[t] = *reinterpret_cast<const U4*>(a.dig + (((ct0 + t) * a.k + i) * a.k + j) * rn + c);
+#pragma unroll
+        for (int t = 0; t < CT; ++t) {
+          s0[t][0] += (uint64_t)d[t].x * e0.x; s0[t][1] += (uint64_t)d[t].y * e0.y;
+          s0[t][2] += (uint64_t)d[t].z * e0.z; s0[t][3] += (uint64_t)d[t].w * e0.w;
+          s1[t][0] += (uint64_t)d[t].x * e1.x; s1[t][1] += (uint64_t)d[t].y * e1.y;
+          s1[t][2] += (uint64_t)d[t].z * e1.z; s1[t][3] += (uint64_t)d[t].w * e1.w;
+        }
       }
       if (i1 < a.k) {
-        for (int q = 0; q < 4; ++q) { s0[q] = reduce64(s0[q], m); s1[q] = reduce64(s1[q], m); }
+#pragma unroll
+        for (int t = 0; t < CT; ++t)
+          for (int q = 0; q < 4; ++q) { s0[t][q] = reduce64(s0[t][q], m); s1[t][q] = reduce64(s1[t][q], m); }
       }
     }
-    U4 r0, r1;
-    r0.x = reduce64(s0[0], m); r0.y = reduce64(s0[1], m); r0.z = reduce64(s0[2], m); r0.w = reduce64(s0[3], m);
-    r1.x = reduce64(s1[0], m); r1.y = reduce64(s1[1], m); r1.z = reduce64(s1[2], m); r1.w = reduce64(s1[3], m);
-    *reinterpret_cast<U4*>(a.acc + ((ct * 2 + 0) * a.k + j) * rn + c) = r0;
-    *reinterpret_cast<U4*>(a.acc + ((ct * 2 + 1) * a.k + j) * rn + c) = r1;
+#pragma unroll
+    for (int t = 0; t < CT; ++t) {
+      U4 r0, r1;
+      r0.x = reduce64(s0[t][0], m); r0.y = reduce64(s0[t][1], m); r0.z = reduce64(s0[t][2], m); r0.w = reduce64(s0[t][3], m);
+      r1.x = reduce64(s1[t][0], m); r1.y = reduce64(s1[t][1], m); r1.z = reduce64(s1[t][2], m); r1.w = reduce64(s1[t][3], m);
+      *reinterpret_cast<U4*>(a.acc + (((ct0 + t) * 2 + 0) * a.k + j) * rn + c) = r0;
+      *reinterpret_cast<U4*>(a.acc + (((ct0 + t) * 2 + 1) * a.k + j) * rn + c) = r1;
+    }
   }
 };
 

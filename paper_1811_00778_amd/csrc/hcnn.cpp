@@ -273,7 +273,7 @@ template <> struct KernelClass<ExtKernel> { static constexpr int id = HCNN_PROF_
 template <int A, int B> struct KernelClass<ExtKernelT<A, B>> { static constexpr int id = HCNN_PROF_BASE_EXT; };
 template <int A, int B> struct KernelClass<ScaleKernelR<A, B>> { static constexpr int id = HCNN_PROF_SCALE; };
 template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
-template <> struct KernelClass<RelinMacKernel> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
+template <int A> struct KernelClass<RelinMacKernel<A>> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
 template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 template <int F> struct KernelClass<MacKernelDirect<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 
@@ -813,12 +813,22 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     if ((e = ntt_dense(c, y, dig, cc * k * k, k, false, kNttLoadDigit))) return e;
     // 7. inner product with the evaluation key
     RelinMacArgs ra;
-    ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n; ra.n_ct = (uint32_t)cc;
+    ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
     // in the plain (ciphertext-major) order every die touches the key tiles of all limbs: 2*k*k*(tiles/8) * 4 KiB
     ra.key_major = (bpr % kXcds == 0 && (size_t)2 * k * k * (bpr / kXcds) * 4096 > ((size_t)1 << 20)) ? 1u : 0u;
     if (c->relin_order == 1) ra.key_major = 0;
     if (c->relin_order == 2 && bpr % kXcds == 0) ra.key_major = 1;
-    if ((e = run<RelinMacKernel>(c, cc * k * bpr, 0, ra))) return e;
+    // groups of kRelinCts ciphertexts share their loads of the key; the remainder goes one by one
+    constexpr int kRelinCts = 4;
+    const size_t full = cc / kRelinCts;
+    if (full) {
+      ra.n_grp = (uint32_t)full; ra.ct_base = 0;
+      if ((e = run<RelinMacKernel<kRelinCts>>(c, full * k * bpr, 0, ra))) return e;
+    }
+    if (cc % kRelinCts) {
+      ra.n_grp = (uint32_t)(cc % kRelinCts); ra.ct_base = (uint32_t)(full * kRelinCts);
+      if ((e = run<RelinMacKernel<1>>(c, (cc % kRelinCts) * k * bpr, 0, ra))) return e;
+    }
     // 8. c'_b = y_b + sum_i evk[i][b] * digit_i : inverse transform with the addition on the way out
     if ((e = ntt_dense(c, acc, out + c0 * ct_words, cc * 2 * k, k, true, kNttStoreAdd, y))) return e;
   }

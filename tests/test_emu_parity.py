@@ -52,6 +52,7 @@ def test_square_relin_tiny_config(backend):
 
 def test_square_relin_chunked_ragged(backend):
     pc.check_square_relin(backend, 1024, 3, n_random=4, n_genuine=1, chunk=2)
+    pc.check_square_relin(backend, 1024, 3, n_random=5, n_genuine=1)      # one group of four sharing key loads + two singles
     pc.check_square_relin(backend, 1024, 3, n_random=2, n_genuine=0, chunk=2, relin_order=1)   # ciphertext-major order forced
 
 
@@ -78,7 +79,7 @@ def test_square_relin_at_a_degree_with_die_aware_block_orders(backend):
     # n = 8192: 8 coefficient tiles per row, the size from which the inner-product kernel orders its
     # workgroups by accelerator die; three ciphertexts so that the ciphertext index is exercised too
     pc.check_square_relin(backend, 8192, 2, n_random=3, n_genuine=0)
-    pc.check_square_relin(backend, 8192, 2, n_random=3, n_genuine=0, relin_order=2)    # key-major order forced
+    pc.check_square_relin(backend, 8192, 2, n_random=6, n_genuine=0, relin_order=2)    # key-major order forced
 
 
 def test_general_hmult(backend):

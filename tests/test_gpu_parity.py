@@ -69,8 +69,9 @@ def test_square_relin_tiny_config(backend):
 def test_square_relin_chunked_ragged(backend):
     say("square_relin chunked n=1024 k=3")
     pc.check_square_relin(backend, 1024, 3, n_random=4, n_genuine=1, chunk=2)
+    pc.check_square_relin(backend, 1024, 3, n_random=5, n_genuine=1)      # one group of four sharing key loads + two singles
     pc.check_square_relin(backend, 1024, 3, n_random=2, n_genuine=0, chunk=2, relin_order=1)   # ciphertext-major order forced
-    pc.check_square_relin(backend, 8192, 2, n_random=3, n_genuine=0, relin_order=2)            # key-major order
+    pc.check_square_relin(backend, 8192, 2, n_random=6, n_genuine=0, relin_order=2)            # key-major order
 
 
 def test_square_relin_exact_comparison_path(backend):
