@@ -411,6 +411,15 @@ int build_tables(hcnn_ctx* c) {
     const uint32_t ninv = h_inv(n % p, p);
     nl.ninv = h_shoup(ninv, p);
     nl.w1ninv = h_shoup(h_mulmod(twi[(size_t)l * n + 1].w, ninv, p), p);
+    const uint32_t ninv_r = h_mulmod(ninv, nl.m.c32, p);                     // c32 = 2^32 mod p
+    nl.ninv_r = h_shoup(ninv_r, p);
+    nl.w1ninv_r = h_shoup(h_mulmod(twi[(size_t)l * n + 1].w, ninv_r, p), p);
+    {
+      uint32_t inv = 1;                                                       // Newton iteration for p^-1 mod 2^32
+      for (int it = 0; it < 5; ++it) inv *= 2u - p * inv;
+      nl.pinv = 0u - inv;
+    }
+    nl.pad[0] = nl.pad[1] = nl.pad[2] = 0;
     mods.push_back(nl.m);
     limbs.push_back(nl);
   }

@@ -59,6 +59,13 @@ HCNN_HD uint32_t reduce64_2p(uint64_t x, const Mod& m) {
   return csub(y + (lo - qb * m.p), 2 * m.p);
 }
 
+// Montgomery reduction: x * 2^-32 mod p up to one extra p, for x < p * 2^32 (in particular for the
+// product of two values below 2p).  pinv = -p^-1 mod 2^32; result in [0, 2p).
+HCNN_HD uint32_t redc_2p(uint64_t x, uint32_t p, uint32_t pinv) {
+  const uint32_t mm = (uint32_t)x * pinv;              // x + mm*p = 0 mod 2^32
+  return (uint32_t)((x + (uint64_t)mm * p) >> 32);     // below 2^62 + 2^62: no overflow
+}
+
 // x mod p up to three extra p: result in [0, 4p) for any x < 2^64.
 HCNN_HD uint32_t reduce64_lazy(uint64_t x, const Mod& m) {
   uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;

@@ -24,6 +24,12 @@ struct NttLimb {
   Mod m;
   ShoupConst ninv;    // n^-1 mod p
   ShoupConst w1ninv;  // (inverse twiddle of node 1) * n^-1 mod p
+  // the tensor-forming loads multiply with a Montgomery reduction, which leaves a factor 2^-32 on every
+  // product; their transforms scale by n^-1 * 2^32 at the end instead of n^-1
+  ShoupConst ninv_r;    // n^-1 * 2^32 mod p
+  ShoupConst w1ninv_r;  // (inverse twiddle of node 1) * n^-1 * 2^32 mod p
+  uint32_t pinv;        // -p^-1 mod 2^32
+  uint32_t pad[3];
 };
 
 // Row r (= workgroup index) belongs to group r / limb_cycle and limb limb_base + r % limb_cycle.
@@ -40,8 +46,9 @@ struct NttLimb {
 //                   `in` holds the first, `aux` the second (same [ct][2][L][n] layout):
 //                   c0^*c0'^, c0^*c1'^ + c1^*c0'^, c1^*c1'^
 //   kNttStoreAdd    inverse only: row (ct, b, j) adds aux row (ct*3+b)*k + j (aux = y) on the way out
-//   kNttStoreLazy   forward only: the output is left lazily reduced in [0, 4p) (for rows whose only reader is
-//                   the tensor-forming load, which reduces 64-bit products of any 32-bit operands)
+//   kNttStoreLazy   forward only: the output is left lazily reduced in [0, 2p) (for rows whose only reader is
+//                   the tensor-forming load: products of two such values are below p * 2^32, the range of
+//                   its Montgomery reduction)
 // The tensor-forming loads also leave their output lazily reduced, in [0, 2p): its only reader multiplies it
 // by a constant with Shoup's method, which takes any 32-bit operand.
 enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4,
@@ -171,7 +178,7 @@ struct NttFwd {
         for (int e = 0; e < NET; e += 4) {
           U4 t;
           if constexpr (IO == kNttStoreLazy) {
-            t.x = v[e + 0]; t.y = v[e + 1]; t.z = v[e + 2]; t.w = v[e + 3];
+            t.x = csub(v[e + 0], two_p); t.y = csub(v[e + 1], two_p); t.z = csub(v[e + 2], two_p); t.w = csub(v[e + 3], two_p);
           } else {
             t.x = csub(csub(v[e + 0], two_p), p);
             t.y = csub(csub(v[e + 1], two_p), p);
@@ -183,7 +190,7 @@ struct NttFwd {
       } else {
 #pragma unroll
         for (int e = 0; e < NET; ++e) {
-          if (kLast) gout[base + (uint32_t)e * TLAST] = IO == kNttStoreLazy ? v[e] : csub(csub(v[e], two_p), p);
+          if (kLast) gout[base + (uint32_t)e * TLAST] = IO == kNttStoreLazy ? csub(v[e], two_p) : csub(csub(v[e], two_p), p);
           else       lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
         }
       }
@@ -266,25 +273,27 @@ struct NttInv {
         for (int e = 0; e < NET; e += 4) {
           U4 t = g4[e / 4];
           if constexpr (IO == kNttLoadTensorMul) {
-            // t = c0^ (b = 0, 1) or c1^ (b = 2);  y = c0'^ (b = 0) or c1'^ (b = 1, 2)
+            // t = c0^ (b = 0, 1) or c1^ (b = 2);  y = c0'^ (b = 0) or c1'^ (b = 1, 2); all in [0, 2p)
             const U4 y = reinterpret_cast<const U4*>(gin2 + base)[e / 4];
-            t.x = mul_mod(t.x, y.x, L.m); t.y = mul_mod(t.y, y.y, L.m);
-            t.z = mul_mod(t.z, y.z, L.m); t.w = mul_mod(t.w, y.w, L.m);
+            t.x = redc_2p((uint64_t)t.x * y.x, p, L.pinv); t.y = redc_2p((uint64_t)t.y * y.y, p, L.pinv);
+            t.z = redc_2p((uint64_t)t.z * y.z, p, L.pinv); t.w = redc_2p((uint64_t)t.w * y.w, p, L.pinv);
             if (comp == 1) {                 // + c1^ * c0'^
               const U4 u = reinterpret_cast<const U4*>(gmul0 + (size_t)a.limb_cycle * N + base)[e / 4];
               const U4 w = reinterpret_cast<const U4*>(gmul1 + base)[e / 4];
-              t.x = add_mod(t.x, mul_mod(u.x, w.x, L.m), p); t.y = add_mod(t.y, mul_mod(u.y, w.y, L.m), p);
-              t.z = add_mod(t.z, mul_mod(u.z, w.z, L.m), p); t.w = add_mod(t.w, mul_mod(u.w, w.w, L.m), p);
+              t.x = csub(t.x + redc_2p((uint64_t)u.x * w.x, p, L.pinv), two_p);
+              t.y = csub(t.y + redc_2p((uint64_t)u.y * w.y, p, L.pinv), two_p);
+              t.z = csub(t.z + redc_2p((uint64_t)u.z * w.z, p, L.pinv), two_p);
+              t.w = csub(t.w + redc_2p((uint64_t)u.w * w.w, p, L.pinv), two_p);
             }
           }
           if constexpr (IO == kNttLoadTensor) {
-            // gin was pointed at c0^ (b = 0, 1) or c1^ (b = 2); only b = 1 needs the second row
+            // gin was pointed at c0^ (b = 0, 1) or c1^ (b = 2); only b = 1 needs the second row.  Products (with
+            // the factor 2^-32 of the reduction) and the doubled cross term stay in [0, 2p), which is what the
+            // first butterflies of the inverse transform take
             U4 y = t;
             if (comp == 1) y = reinterpret_cast<const U4*>(gin2 + base)[e / 4];
-            // products and the doubled cross term stay lazily reduced in [0, 2p), which is what the first
-            // butterflies of the inverse transform take
-            t.x = reduce64_2p((uint64_t)t.x * y.x, L.m); t.y = reduce64_2p((uint64_t)t.y * y.y, L.m);
-            t.z = reduce64_2p((uint64_t)t.z * y.z, L.m); t.w = reduce64_2p((uint64_t)t.w * y.w, L.m);
+            t.x = redc_2p((uint64_t)t.x * y.x, p, L.pinv); t.y = redc_2p((uint64_t)t.y * y.y, p, L.pinv);
+            t.z = redc_2p((uint64_t)t.z * y.z, p, L.pinv); t.w = redc_2p((uint64_t)t.w * y.w, p, L.pinv);
             if (comp == 1) { t.x = csub(2 * t.x, two_p); t.y = csub(2 * t.y, two_p); t.z = csub(2 * t.z, two_p); t.w = csub(2 * t.w, two_p); }
           }
           v[e + 0] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
@@ -296,13 +305,13 @@ struct NttInv {
             uint32_t t = gin[base + (uint32_t)e * TLAST];
             if constexpr (IO == kNttLoadTensorMul) {
               const uint32_t idx = base + (uint32_t)e * TLAST;
-              t = mul_mod(t, gin2[idx], L.m);
+              t = redc_2p((uint64_t)t * gin2[idx], p, L.pinv);
               if (comp == 1)
-                t = add_mod(t, mul_mod(gmul0[(size_t)a.limb_cycle * N + idx], gmul1[idx], L.m), p);
+                t = csub(t + redc_2p((uint64_t)gmul0[(size_t)a.limb_cycle * N + idx] * gmul1[idx], p, L.pinv), two_p);
             }
             if constexpr (IO == kNttLoadTensor) {
               const uint32_t u = comp == 1 ? gin2[base + (uint32_t)e * TLAST] : t;
-              t = reduce64_2p((uint64_t)t * u, L.m);
+              t = redc_2p((uint64_t)t * u, p, L.pinv);
               if (comp == 1) t = csub(2 * t, two_p);
             }
             v[e] = t;
@@ -318,14 +327,16 @@ struct NttInv {
         const bool top = kLast && l == 0;                 // node 1: fold in n^-1
 #pragma unroll
         for (int h = 0; h < (1 << l); ++h) {
-          const ShoupConst w = top ? L.w1ninv : ldc(tw, (root << l) + h);
+          constexpr bool kMont = IO == kNttLoadTensor || IO == kNttLoadTensorMul;
+          const ShoupConst w = top ? (kMont ? L.w1ninv_r : L.w1ninv) : ldc(tw, (root << l) + h);
+          const ShoupConst nv = kMont ? L.ninv_r : L.ninv;
 #pragma unroll
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
             const uint32_t X = v[ia], Y = v[ib];
             const uint32_t S = X + Y;                                   // [0, 4p)
             const uint32_t D = X + two_p - Y;                           // (0, 4p)
-            v[ia] = top ? shoup_lazy(S, L.ninv.w, L.ninv.ws, p) : csub(S, two_p);
+            v[ia] = top ? shoup_lazy(S, nv.w, nv.ws, p) : csub(S, two_p);
             v[ib] = shoup_lazy(D, w.w, w.ws, p);                        // [0, 2p)
           }
         }
