@@ -41,6 +41,9 @@ struct BConvDev {
   const uint32_t* ginv;      // [ks][ks] ginv[i*ks + l] = m_l^-1 mod m_i, l < i
   const uint32_t* half;      // [ks]   mixed-radix digits of (M-1)/2
   const Mod* dst_mod;        // [kd]
+  const uint32_t* dst_pinv;  // [kd]   -m'_j^-1 mod 2^32 (destinations that are RNS primes)
+  // destination constants; for RNS-prime destinations they carry an extra factor 2^32 (Montgomery form), which
+  // the reduction of the accumulated sum takes out again (mont_reduce)
   const uint32_t* Bp;        // [ks][kd]
   const uint32_t* BpT;       // [kd][ks]  the same constants, transposed
   const uint32_t* Vp;        // [kd]
@@ -111,16 +114,23 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
   return bconv_round(S, band, exact, fallback_counter);
 }
 
-// Residue of the converted integer modulo destination j; `extra` (< 2^61) is added before reducing.
+// Residue of the converted integer modulo destination j; `extra` (< 2^61, already carrying the factor 2^32 of the
+// Montgomery-form constants) is added before reducing.
 HCNN_HD uint32_t bconv_output(const BConvDev& bc, const uint32_t* zcol, int stride, uint32_t v, uint32_t j,
                               uint64_t extra = 0) {
   const Mod dm = ldc(bc.dst_mod, j);
+  const uint32_t pinv = ldc(bc.dst_pinv, j);
   uint64_t acc = extra + (uint64_t)v * ldc(bc.Vp, j);
+  uint32_t room = kMontFirst - 2;                     // `extra` may take the room of two products
   for (uint32_t i = 0; i < bc.ks; ++i) {
+    if (room == 0) {
+      acc = (uint64_t)mont_reduce(acc, dm, pinv) << 32;
+      room = kMontNext;
+    }
     acc += (uint64_t)zcol[i * stride] * ldc(bc.Bp, i * bc.kd + j);
-    if ((i & 7u) == 7u) acc = reduce64(acc, dm);
+    --room;
   }
-  return reduce64(acc, dm);
+  return mont_reduce(acc, dm, pinv);
 }
 
 // ---------------------------------------------------------------- q -> q u p extension
@@ -195,14 +205,16 @@ struct ExtKernelT {
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
       const Mod dm = ldc(a.bc.dst_mod, j);
+      const uint32_t pinv = ldc(a.bc.dst_pinv, j);
       const uint32_t* bt = a.bc.BpT + (size_t)j * K;
       uint64_t acc = (uint64_t)v * ldc(a.bc.Vp, j);
 #pragma unroll
       for (int i = 0; i < K; ++i) {
+        // folds after kMontFirst - 1 products, then after every kMontNext more
+        if (i >= kMontFirst - 1 && (i - (kMontFirst - 1)) % kMontNext == 0) acc = (uint64_t)mont_reduce(acc, dm, pinv) << 32;
         acc += (uint64_t)z[i] * ldc(bt, i);
-        if ((i % 14) == 12 && i + 1 < K) acc = reduce64(acc, dm);
       }
-      dst[(size_t)(K + j) * n] = reduce64(acc, dm);
+      dst[(size_t)(K + j) * n] = mont_reduce(acc, dm, pinv);
     }
   }
 };
@@ -261,7 +273,6 @@ template <int K, int KP>
 struct ScaleKernelR {
   static constexpr int kThreads = kEwThreads;
   static constexpr int kPhases = 1;
-  static constexpr int kCadence = 14;      // products below 2^60 that fit a 64-bit sum with room to spare
   struct Regs {};
   static size_t lds_bytes() { return (size_t)(K > KP ? K : KP) * kThreads * 4; }
   template <int PH>
@@ -300,38 +311,44 @@ struct ScaleKernelR {
     for (int i = 0; i < K; ++i) out_acc[i] = 0;
     uint32_t S2 = 0;
     uint32_t dp_next = src[(size_t)K * n];
+    uint32_t room = kMontFirst;              // products that out_acc may still take before a fold
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
       const uint32_t dpj = dp_next;
       if (j + 1 < (uint32_t)KP) dp_next = src[(size_t)(K + j + 1) * n];
       const Mod dm = ldc(a.to_p.dst_mod, j);
+      const uint32_t dpinv = ldc(a.to_p.dst_pinv, j);
+      // d'_j is below 2p (the tensor's transform leaves it lazily reduced): its product takes the room of two
       uint64_t acc = (uint64_t)dpj * ldc(a.tq_inv, j) + (uint64_t)v * ldc(a.to_p.Vp, j);
       const uint32_t* bt = a.to_p.BpT + (size_t)j * K;
 #pragma unroll
       for (int i = 0; i < K; ++i) {
+        if (i >= kMontFirst - 3 && (i - (kMontFirst - 3)) % kMontNext == 0) acc = (uint64_t)mont_reduce(acc, dm, dpinv) << 32;
         acc += (uint64_t)z[i] * ldc(bt, i);
-        if ((i % kCadence) == kCadence - 2 && i + 1 < K) acc = reduce64(acc, dm);   // two extra terms came first
       }
-      const uint32_t yj = reduce64(acc, dm);
+      const uint32_t yj = mont_reduce(acc, dm, dpinv);
       col[j * kThreads] = yj;
       const Mod sm = ldc(a.to_q.src_mod, j);
       const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm.p);
       S2 += frac_est(z2, sm);
       const uint32_t* b2 = a.to_q.Bp + (size_t)j * K;
+      if (room == 0) {
+#pragma unroll
+        for (int i = 0; i < K; ++i)
+          out_acc[i] = (uint64_t)mont_reduce(out_acc[i], ldc(a.to_q.dst_mod, i), ldc(a.to_q.dst_pinv, i)) << 32;
+        room = kMontNext;
+      }
 #pragma unroll
       for (int i = 0; i < K; ++i) out_acc[i] += (uint64_t)z2 * ldc(b2, i);
-      if ((j % kCadence) == kCadence - 1) {
-#pragma unroll
-        for (int i = 0; i < K; ++i) out_acc[i] = reduce64(out_acc[i], ldc(a.to_q.dst_mod, i));
-      }
+      --room;
     }
     auto exact_p = [&]() { return garner_gt_half(a.to_q, col, kThreads); };
     const uint32_t v2 = bconv_round(S2, a.band, exact_p, a.fallback_counter);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      const Mod dm = ldc(a.to_q.dst_mod, i);
-      // at most kCadence-1 products since the last reduction, plus a residue, plus v2*Vp < 2^35
-      dst[(size_t)i * n] = reduce64(out_acc[i] + (uint64_t)v2 * ldc(a.to_q.Vp, i), dm);
+      // the sum holds at most kMontFirst products (or a folded value and kMontNext), plus v2*Vp < 2^36
+      dst[(size_t)i * n] = mont_reduce(out_acc[i] + (uint64_t)v2 * ldc(a.to_q.Vp, i), ldc(a.to_q.dst_mod, i),
+                                       ldc(a.to_q.dst_pinv, i));
     }
   }
 };

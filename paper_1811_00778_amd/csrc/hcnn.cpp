@@ -105,6 +105,13 @@ uint32_t h_brev(uint32_t v, int bits) {
   return r;
 }
 
+// -p^-1 mod 2^32 for odd p (Newton iteration, doubling the number of correct bits each step)
+uint32_t h_neg_inv32(uint32_t p) {
+  uint32_t inv = 1;
+  for (int it = 0; it < 5; ++it) inv *= 2u - p * inv;
+  return 0u - inv;
+}
+
 ShoupConst h_shoup(uint32_t w, uint32_t p) {
   ShoupConst c;
   c.w = w;
@@ -208,7 +215,7 @@ struct BConvHost {
   uint32_t ks = 0, kd = 0;
   std::vector<Mod> src_mod, dst_mod;
   std::vector<ShoupConst> zmul, xmul;
-  std::vector<uint32_t> ginv, half, Bp, BpT, Vp;
+  std::vector<uint32_t> ginv, half, Bp, BpT, Vp, dst_pinv;
 };
 
 struct hcnn_ctx {
@@ -325,6 +332,8 @@ int fold_profile(hcnn_ctx* c) {
 //   zfac[i]   extra factor folded into z_i (1 or t), also used as xmul
 //   fold_inv  when true the tables give -(x * M^-1): Bp = m'_j - m_i^-1, Vp = 1
 //             otherwise they give x:                 Bp = M/m_i mod m'_j, Vp = m'_j - M mod m'_j
+//   dst_is_rns_prime  the destinations are ciphertext / auxiliary primes: Bp and Vp are stored with an extra factor
+//             2^32 mod m'_j (Montgomery form) and dst_pinv holds -m'_j^-1 mod 2^32
 BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_t>& dst, uint64_t zfac,
                      bool fold_inv, bool dst_is_rns_prime) {
   BConvHost h;
@@ -360,6 +369,14 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
     for (uint32_t i = 0; i < h.ks; ++i)
       h.Bp[(size_t)i * h.kd + j] = fold_inv ? mj - h_inv(src[i] % mj, mj) : h_prod_mod(src, (int)i, mj);
     h.Vp[j] = fold_inv ? 1u : (mj - h_prod_mod(src, -1, mj)) % mj;
+    if (dst_is_rns_prime) {
+      const uint32_t r32 = (uint32_t)((1ull << 32) % mj);
+      for (uint32_t i = 0; i < h.ks; ++i) h.Bp[(size_t)i * h.kd + j] = h_mulmod(h.Bp[(size_t)i * h.kd + j], r32, mj);
+      h.Vp[j] = h_mulmod(h.Vp[j], r32, mj);
+      h.dst_pinv.push_back(h_neg_inv32(mj));
+    } else {
+      h.dst_pinv.push_back(0);
+    }
   }
   h.BpT.assign((size_t)h.ks * h.kd, 0);
   for (uint32_t i = 0; i < h.ks; ++i)
@@ -369,7 +386,7 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
 
 int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
   int e;
-  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* BT; uint32_t* Mm;
+  Mod* sm; Mod* dm; ShoupConst* zm; ShoupConst* xm; uint32_t* gi; uint32_t* hf; uint32_t* B; uint32_t* BT; uint32_t* Mm; uint32_t* pi;
   if ((e = upload(c, h.src_mod, &sm))) return e;
   if ((e = upload(c, h.dst_mod, &dm))) return e;
   if ((e = upload(c, h.zmul, &zm))) return e;
@@ -379,9 +396,10 @@ int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
   if ((e = upload(c, h.Bp, &B))) return e;
   if ((e = upload(c, h.BpT, &BT))) return e;
   if ((e = upload(c, h.Vp, &Mm))) return e;
+  if ((e = upload(c, h.dst_pinv, &pi))) return e;
   d->ks = h.ks; d->kd = h.kd;
   d->src_mod = sm; d->dst_mod = dm; d->zmul = zm; d->xmul = xm;
-  d->ginv = gi; d->half = hf; d->Bp = B; d->BpT = BT; d->Vp = Mm;
+  d->ginv = gi; d->half = hf; d->Bp = B; d->BpT = BT; d->Vp = Mm; d->dst_pinv = pi;
   return 0;
 }
 
@@ -414,11 +432,7 @@ int build_tables(hcnn_ctx* c) {
     const uint32_t ninv_r = h_mulmod(ninv, nl.m.c32, p);                     // c32 = 2^32 mod p
     nl.ninv_r = h_shoup(ninv_r, p);
     nl.w1ninv_r = h_shoup(h_mulmod(twi[(size_t)l * n + 1].w, ninv_r, p), p);
-    {
-      uint32_t inv = 1;                                                       // Newton iteration for p^-1 mod 2^32
-      for (int it = 0; it < 5; ++it) inv *= 2u - p * inv;
-      nl.pinv = 0u - inv;
-    }
+    nl.pinv = h_neg_inv32(p);
     nl.pad[0] = nl.pad[1] = nl.pad[2] = 0;
     mods.push_back(nl.m);
     limbs.push_back(nl);
@@ -466,7 +480,8 @@ int build_tables(hcnn_ctx* c) {
     std::vector<uint32_t> tq;
     for (uint32_t j = 0; j < c->kp; ++j) {
       const uint32_t pj = c->p[j];
-      tq.push_back(h_mulmod((uint32_t)(c->t % pj), h_inv(h_prod_mod(c->q, -1, pj), pj), pj));
+      // t * q^-1 mod p_j, with the factor 2^32 of the Montgomery-form constants it is summed with
+      tq.push_back(h_mulmod(h_mulmod((uint32_t)(c->t % pj), h_inv(h_prod_mod(c->q, -1, pj), pj), pj), (uint32_t)((1ull << 32) % pj), pj));
     }
     if ((e = upload(c, tq, &c->d_tq_inv))) return e;
   }

@@ -66,18 +66,30 @@ HCNN_HD uint32_t redc_2p(uint64_t x, uint32_t p, uint32_t pinv) {
   return (uint32_t)((x + (uint64_t)mm * p) >> 32);     // below 2^62 + 2^62: no overflow
 }
 
+// x mod p for x < 2^32, canonical.
+HCNN_HD uint32_t reduce32(uint32_t x, const Mod& m) {
+  uint32_t qb = mulhi32(x, m.mu) >> 29;
+  return csub(x - qb * m.p, m.p);
+}
+
+// x * 2^-32 mod p, canonical, for any x < 3 * 2^62: a Montgomery step (result below 2^32) followed by a
+// one-word Barrett step.  Used for sums of products whose constant factors carry an extra 2^32.
+HCNN_HD uint32_t mont_reduce(uint64_t x, const Mod& m, uint32_t pinv) {
+  const uint32_t mm = (uint32_t)x * pinv;
+  const uint32_t u = (uint32_t)((x + (uint64_t)mm * m.p) >> 32);     // x + mm*p < 3*2^62 + 2^62
+  return reduce32(u, m);
+}
+// how many products of two values below 2^30 such a sum may hold: kMontFirst when it starts from zero (plus
+// small terms), kMontNext more after a fold (the folded value, below p * 2^32, takes the room of four)
+constexpr int kMontFirst = 11;
+constexpr int kMontNext = 7;
+
 // x mod p up to three extra p: result in [0, 4p) for any x < 2^64.
 HCNN_HD uint32_t reduce64_lazy(uint64_t x, const Mod& m) {
   uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
   uint32_t y = shoup_lazy(hi, m.c32, m.c32s, m.p);
   uint32_t qb = mulhi32(lo, m.mu) >> 29;
   return y + (lo - qb * m.p);
-}
-
-// x mod p for x < 2^32, canonical.
-HCNN_HD uint32_t reduce32(uint32_t x, const Mod& m) {
-  uint32_t qb = mulhi32(x, m.mu) >> 29;
-  return csub(x - qb * m.p, m.p);
 }
 
 HCNN_HD uint32_t mul_mod(uint32_t a, uint32_t b, const Mod& m) { return reduce64((uint64_t)a * b, m); }
