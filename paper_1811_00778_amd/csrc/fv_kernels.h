@@ -42,12 +42,17 @@ struct BConvDev {
   const uint32_t* half;      // [ks]   mixed-radix digits of (M-1)/2
   const Mod* dst_mod;        // [kd]
   const uint32_t* dst_pinv;  // [kd]   -m'_j^-1 mod 2^32 (destinations that are RNS primes)
-  // destination constants; for RNS-prime destinations they carry an extra factor 2^32 (Montgomery form), which
-  // the reduction of the accumulated sum takes out again (mont_reduce)
+  uint32_t mont;             // 1: the destination constants carry an extra factor 2^32 (Montgomery form), which the
+                             // reduction of the accumulated sum takes out again (mont_reduce); see bconv_use_mont
   const uint32_t* Bp;        // [ks][kd]
   const uint32_t* BpT;       // [kd][ks]  the same constants, transposed
   const uint32_t* Vp;        // [kd]
 };
+
+// Montgomery form is used where the whole sum of a destination residue (ks products plus `extra` more of the same
+// size) fits the 64-bit accumulator without an intermediate fold; longer sums keep plain constants and the
+// two-word Barrett reduction, which leaves room for 15 products between folds.
+HCNN_HOSTDEV constexpr bool bconv_use_mont(uint32_t ks, uint32_t extra) { return ks + extra <= kMontRoom; }
 
 constexpr uint32_t kFracBits = 26;
 constexpr uint32_t kFracOne = 1u << kFracBits;
@@ -114,23 +119,21 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
   return bconv_round(S, band, exact, fallback_counter);
 }
 
-// Residue of the converted integer modulo destination j; `extra` (< 2^61, already carrying the factor 2^32 of the
-// Montgomery-form constants) is added before reducing.
+// Residue of the converted integer modulo destination j; `extra` (below 2^60, in the form of the table's constants)
+// is added before reducing.
 HCNN_HD uint32_t bconv_output(const BConvDev& bc, const uint32_t* zcol, int stride, uint32_t v, uint32_t j,
                               uint64_t extra = 0) {
   const Mod dm = ldc(bc.dst_mod, j);
-  const uint32_t pinv = ldc(bc.dst_pinv, j);
   uint64_t acc = extra + (uint64_t)v * ldc(bc.Vp, j);
-  uint32_t room = kMontFirst - 2;                     // `extra` may take the room of two products
-  for (uint32_t i = 0; i < bc.ks; ++i) {
-    if (room == 0) {
-      acc = (uint64_t)mont_reduce(acc, dm, pinv) << 32;
-      room = kMontNext;
-    }
-    acc += (uint64_t)zcol[i * stride] * ldc(bc.Bp, i * bc.kd + j);
-    --room;
+  if (bc.mont) {
+    for (uint32_t i = 0; i < bc.ks; ++i) acc += (uint64_t)zcol[i * stride] * ldc(bc.Bp, i * bc.kd + j);
+    return mont_reduce(acc, dm, ldc(bc.dst_pinv, j));
   }
-  return mont_reduce(acc, dm, pinv);
+  for (uint32_t i = 0; i < bc.ks; ++i) {
+    acc += (uint64_t)zcol[i * stride] * ldc(bc.Bp, i * bc.kd + j);
+    if ((i & 7u) == 7u) acc = reduce64(acc, dm);
+  }
+  return reduce64(acc, dm);
 }
 
 // ---------------------------------------------------------------- q -> q u p extension
@@ -205,16 +208,20 @@ struct ExtKernelT {
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
       const Mod dm = ldc(a.bc.dst_mod, j);
-      const uint32_t pinv = ldc(a.bc.dst_pinv, j);
       const uint32_t* bt = a.bc.BpT + (size_t)j * K;
       uint64_t acc = (uint64_t)v * ldc(a.bc.Vp, j);
+      if constexpr (bconv_use_mont(K, 0)) {
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        // folds after kMontFirst - 1 products, then after every kMontNext more
-        if (i >= kMontFirst - 1 && (i - (kMontFirst - 1)) % kMontNext == 0) acc = (uint64_t)mont_reduce(acc, dm, pinv) << 32;
-        acc += (uint64_t)z[i] * ldc(bt, i);
+        for (int i = 0; i < K; ++i) acc += (uint64_t)z[i] * ldc(bt, i);
+        dst[(size_t)(K + j) * n] = mont_reduce(acc, dm, ldc(a.bc.dst_pinv, j));
+      } else {
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+          acc += (uint64_t)z[i] * ldc(bt, i);
+          if ((i % 14) == 12 && i + 1 < K) acc = reduce64(acc, dm);
+        }
+        dst[(size_t)(K + j) * n] = reduce64(acc, dm);
       }
-      dst[(size_t)(K + j) * n] = mont_reduce(acc, dm, pinv);
     }
   }
 };
@@ -257,7 +264,8 @@ struct ScaleKernel {
     auto in_q = [&](uint32_t i) { return src[(size_t)i * n]; };
     const uint32_t v = bconv_prepare(a.to_p, in_q, zcol, gcol, kThreads, a.band, a.fallback_counter);
     for (uint32_t j = 0; j < kp; ++j) {
-      const uint64_t extra = (uint64_t)src[(size_t)(k + j) * n] * ldc(a.tq_inv, j);
+      // d'_j arrives in [0, 2p): made canonical so that its product takes the room of one
+      const uint64_t extra = (uint64_t)csub(src[(size_t)(k + j) * n], ldc(a.to_p.dst_mod, j).p) * ldc(a.tq_inv, j);
       ycol[j * kThreads] = bconv_output(a.to_p, zcol, kThreads, v, j, extra);
     }
     auto in_p = [&](uint32_t j) { return ycol[j * kThreads]; };
@@ -306,49 +314,58 @@ struct ScaleKernelR {
     };
     const uint32_t v = bconv_round(S, a.band, exact_q, a.fallback_counter);
 
+    // to_p sums K products and the term of d'_j (which arrives in [0, 2p): it takes the room of two unless it is made
+    // canonical first); to_q sums KP products.  Each uses Montgomery-form constants iff the host built them so.
+    constexpr bool kMontP = bconv_use_mont(K, 1), kCanonDp = !bconv_use_mont(K, 2);
+    constexpr bool kMontQ = bconv_use_mont(KP, 0);
+    constexpr int kCadence = 14;             // plain form: products below 2^60 between two-word reductions
     uint64_t out_acc[K];
 #pragma unroll
     for (int i = 0; i < K; ++i) out_acc[i] = 0;
     uint32_t S2 = 0;
     uint32_t dp_next = src[(size_t)K * n];
-    uint32_t room = kMontFirst;              // products that out_acc may still take before a fold
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
-      const uint32_t dpj = dp_next;
+      uint32_t dpj = dp_next;
       if (j + 1 < (uint32_t)KP) dp_next = src[(size_t)(K + j + 1) * n];
       const Mod dm = ldc(a.to_p.dst_mod, j);
-      const uint32_t dpinv = ldc(a.to_p.dst_pinv, j);
-      // d'_j is below 2p (the tensor's transform leaves it lazily reduced): its product takes the room of two
+      if constexpr (kCanonDp) dpj = csub(dpj, dm.p);
       uint64_t acc = (uint64_t)dpj * ldc(a.tq_inv, j) + (uint64_t)v * ldc(a.to_p.Vp, j);
       const uint32_t* bt = a.to_p.BpT + (size_t)j * K;
+      uint32_t yj;
+      if constexpr (kMontP) {
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        if (i >= kMontFirst - 3 && (i - (kMontFirst - 3)) % kMontNext == 0) acc = (uint64_t)mont_reduce(acc, dm, dpinv) << 32;
-        acc += (uint64_t)z[i] * ldc(bt, i);
+        for (int i = 0; i < K; ++i) acc += (uint64_t)z[i] * ldc(bt, i);
+        yj = mont_reduce(acc, dm, ldc(a.to_p.dst_pinv, j));
+      } else {
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+          acc += (uint64_t)z[i] * ldc(bt, i);
+          if ((i % kCadence) == kCadence - 2 && i + 1 < K) acc = reduce64(acc, dm);   // the term of d'_j came first
+        }
+        yj = reduce64(acc, dm);
       }
-      const uint32_t yj = mont_reduce(acc, dm, dpinv);
       col[j * kThreads] = yj;
       const Mod sm = ldc(a.to_q.src_mod, j);
       const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm.p);
       S2 += frac_est(z2, sm);
       const uint32_t* b2 = a.to_q.Bp + (size_t)j * K;
-      if (room == 0) {
-#pragma unroll
-        for (int i = 0; i < K; ++i)
-          out_acc[i] = (uint64_t)mont_reduce(out_acc[i], ldc(a.to_q.dst_mod, i), ldc(a.to_q.dst_pinv, i)) << 32;
-        room = kMontNext;
-      }
 #pragma unroll
       for (int i = 0; i < K; ++i) out_acc[i] += (uint64_t)z2 * ldc(b2, i);
-      --room;
+      if constexpr (!kMontQ) {
+        if ((j % kCadence) == kCadence - 1) {
+#pragma unroll
+          for (int i = 0; i < K; ++i) out_acc[i] = reduce64(out_acc[i], ldc(a.to_q.dst_mod, i));
+        }
+      }
     }
     auto exact_p = [&]() { return garner_gt_half(a.to_q, col, kThreads); };
     const uint32_t v2 = bconv_round(S2, a.band, exact_p, a.fallback_counter);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      // the sum holds at most kMontFirst products (or a folded value and kMontNext), plus v2*Vp < 2^36
-      dst[(size_t)i * n] = mont_reduce(out_acc[i] + (uint64_t)v2 * ldc(a.to_q.Vp, i), ldc(a.to_q.dst_mod, i),
-                                       ldc(a.to_q.dst_pinv, i));
+      const Mod dm = ldc(a.to_q.dst_mod, i);
+      const uint64_t sum = out_acc[i] + (uint64_t)v2 * ldc(a.to_q.Vp, i);      // v2*Vp < 2^36
+      dst[(size_t)i * n] = kMontQ ? mont_reduce(sum, dm, ldc(a.to_q.dst_pinv, i)) : reduce64(sum, dm);
     }
   }
 };

@@ -216,6 +216,7 @@ struct BConvHost {
   std::vector<Mod> src_mod, dst_mod;
   std::vector<ShoupConst> zmul, xmul;
   std::vector<uint32_t> ginv, half, Bp, BpT, Vp, dst_pinv;
+  uint32_t mont = 0;
 };
 
 struct hcnn_ctx {
@@ -332,10 +333,11 @@ int fold_profile(hcnn_ctx* c) {
 //   zfac[i]   extra factor folded into z_i (1 or t), also used as xmul
 //   fold_inv  when true the tables give -(x * M^-1): Bp = m'_j - m_i^-1, Vp = 1
 //             otherwise they give x:                 Bp = M/m_i mod m'_j, Vp = m'_j - M mod m'_j
-//   dst_is_rns_prime  the destinations are ciphertext / auxiliary primes: Bp and Vp are stored with an extra factor
-//             2^32 mod m'_j (Montgomery form) and dst_pinv holds -m'_j^-1 mod 2^32
+//   dst_is_rns_prime  the destinations are ciphertext / auxiliary primes (dst_pinv holds -m'_j^-1 mod 2^32)
+//   extra_terms       further products of the same size that the kernels add to each destination sum; when the
+//             whole sum fits (bconv_use_mont) Bp and Vp are stored with an extra factor 2^32 mod m'_j (Montgomery form)
 BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_t>& dst, uint64_t zfac,
-                     bool fold_inv, bool dst_is_rns_prime) {
+                     bool fold_inv, bool dst_is_rns_prime, uint32_t extra_terms = 0) {
   BConvHost h;
   h.ks = (uint32_t)src.size();
   h.kd = (uint32_t)dst.size();
@@ -369,14 +371,13 @@ BConvHost make_bconv(const std::vector<uint32_t>& src, const std::vector<uint32_
     for (uint32_t i = 0; i < h.ks; ++i)
       h.Bp[(size_t)i * h.kd + j] = fold_inv ? mj - h_inv(src[i] % mj, mj) : h_prod_mod(src, (int)i, mj);
     h.Vp[j] = fold_inv ? 1u : (mj - h_prod_mod(src, -1, mj)) % mj;
-    if (dst_is_rns_prime) {
+    h.mont = (dst_is_rns_prime && bconv_use_mont(h.ks, extra_terms)) ? 1u : 0u;
+    if (h.mont) {
       const uint32_t r32 = (uint32_t)((1ull << 32) % mj);
       for (uint32_t i = 0; i < h.ks; ++i) h.Bp[(size_t)i * h.kd + j] = h_mulmod(h.Bp[(size_t)i * h.kd + j], r32, mj);
       h.Vp[j] = h_mulmod(h.Vp[j], r32, mj);
-      h.dst_pinv.push_back(h_neg_inv32(mj));
-    } else {
-      h.dst_pinv.push_back(0);
     }
+    h.dst_pinv.push_back(dst_is_rns_prime ? h_neg_inv32(mj) : 0u);
   }
   h.BpT.assign((size_t)h.ks * h.kd, 0);
   for (uint32_t i = 0; i < h.ks; ++i)
@@ -399,7 +400,7 @@ int upload_bconv(hcnn_ctx* c, const BConvHost& h, BConvDev* d) {
   if ((e = upload(c, h.dst_pinv, &pi))) return e;
   d->ks = h.ks; d->kd = h.kd;
   d->src_mod = sm; d->dst_mod = dm; d->zmul = zm; d->xmul = xm;
-  d->ginv = gi; d->half = hf; d->Bp = B; d->BpT = BT; d->Vp = Mm; d->dst_pinv = pi;
+  d->ginv = gi; d->half = hf; d->Bp = B; d->BpT = BT; d->Vp = Mm; d->dst_pinv = pi; d->mont = h.mont;
   return 0;
 }
 
@@ -472,7 +473,7 @@ int build_tables(hcnn_ctx* c) {
   }
   if (c->kp) {
     BConvHost h_ext = make_bconv(c->q, c->p, 1, false, true);
-    BConvHost h_to_p = make_bconv(c->q, c->p, c->t, true, true);
+    BConvHost h_to_p = make_bconv(c->q, c->p, c->t, true, true, 1);      // + the term of d'_j
     BConvHost h_to_q = make_bconv(c->p, c->q, 1, false, true);
     if ((e = upload_bconv(c, h_ext, &c->ext))) return e;
     if ((e = upload_bconv(c, h_to_p, &c->to_p))) return e;
@@ -480,8 +481,10 @@ int build_tables(hcnn_ctx* c) {
     std::vector<uint32_t> tq;
     for (uint32_t j = 0; j < c->kp; ++j) {
       const uint32_t pj = c->p[j];
-      // t * q^-1 mod p_j, with the factor 2^32 of the Montgomery-form constants it is summed with
-      tq.push_back(h_mulmod(h_mulmod((uint32_t)(c->t % pj), h_inv(h_prod_mod(c->q, -1, pj), pj), pj), (uint32_t)((1ull << 32) % pj), pj));
+      // t * q^-1 mod p_j, in the form of the constants it is summed with
+      uint32_t v = h_mulmod((uint32_t)(c->t % pj), h_inv(h_prod_mod(c->q, -1, pj), pj), pj);
+      if (h_to_p.mont) v = h_mulmod(v, (uint32_t)((1ull << 32) % pj), pj);
+      tq.push_back(v);
     }
     if ((e = upload(c, tq, &c->d_tq_inv))) return e;
   }

@@ -79,10 +79,8 @@ HCNN_HD uint32_t mont_reduce(uint64_t x, const Mod& m, uint32_t pinv) {
   const uint32_t u = (uint32_t)((x + (uint64_t)mm * m.p) >> 32);     // x + mm*p < 3*2^62 + 2^62
   return reduce32(u, m);
 }
-// how many products of two values below 2^30 such a sum may hold: kMontFirst when it starts from zero (plus
-// small terms), kMontNext more after a fold (the folded value, below p * 2^32, takes the room of four)
-constexpr int kMontFirst = 11;
-constexpr int kMontNext = 7;
+// such a sum may hold kMontRoom products of two values below 2^30 (11 * 2^60 plus small terms < 3 * 2^62)
+constexpr uint32_t kMontRoom = 11;
 
 // x mod p up to three extra p: result in [0, 4p) for any x < 2^64.
 HCNN_HD uint32_t reduce64_lazy(uint64_t x, const Mod& m) {

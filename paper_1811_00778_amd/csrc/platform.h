@@ -20,12 +20,14 @@
 
 #ifdef HCNN_HOSTEMU
 #define HCNN_HD inline
+#define HCNN_HOSTDEV inline
 #define HCNN_DEVICE_CODE 0
 typedef int hcnn_hip_error_t;
 typedef void* hcnn_stream_t;
 #else
 #include <hip/hip_runtime.h>
 #define HCNN_HD __device__ __forceinline__
+#define HCNN_HOSTDEV __host__ __device__ inline
 typedef hipError_t hcnn_hip_error_t;
 typedef hipStream_t hcnn_stream_t;
 #endif
