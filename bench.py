@@ -304,11 +304,12 @@ def main():
             L_ = k + len(p)
             row4 = 4 * n
             if dom == "ntt_fwd":
-                parts = [((ntt_buf.numel() // n + n_ct * 2 * L_) * 2 * row4, 1.078),       # plain rows
-                         (n_ct * k * k * row4 + n_ct * k * row4, 1.030)]                    # digit-reducing load
+                parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
+                         (n_ct * 2 * L_ * 2 * row4, 1.077),                                 # extended operands
+                         (n_ct * k * k * row4 + n_ct * k * row4, 1.030)]                    # digit load
             else:
                 parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
-                         (n_ct * 3 * L_ * row4 + n_ct * 2 * L_ * row4, 1.130),              # tensor-forming load
+                         (n_ct * 3 * L_ * row4 + n_ct * 2 * L_ * row4, 1.134),              # tensor-forming load
                          (n_ct * 2 * k * 3 * row4, 1.008)]                                  # adding store
             per_step_launches = 3
             bytes_per_launch = sum(b for b, _ in parts) / per_step_launches
