@@ -213,7 +213,11 @@ struct ExtKernelT {
       if constexpr (bconv_use_mont(K, 0)) {
 #pragma unroll
         for (int i = 0; i < K; ++i) acc += (uint64_t)z[i] * ldc(bt, i);
-        dst[(size_t)(K + j) * n] = mont_reduce(acc, dm, ldc(a.bc.dst_pinv, j));
+        // The forward transform that reads these rows takes any value below 4p.  A sum of K products leaves the
+        // Montgomery step below K*2^28 + p; for K <= 9 one conditional subtraction of 2p brings that under
+        // max(2p, 9*2^28 - p) < 4p for every p > 2^29.
+        if constexpr (K <= 9) dst[(size_t)(K + j) * n] = csub(mont_step(acc, dm.p, ldc(a.bc.dst_pinv, j)), 2 * dm.p);
+        else                  dst[(size_t)(K + j) * n] = mont_reduce(acc, dm, ldc(a.bc.dst_pinv, j));
       } else {
 #pragma unroll
         for (int i = 0; i < K; ++i) {
@@ -336,16 +340,16 @@ struct ScaleKernelR {
       if constexpr (kMontP) {
 #pragma unroll
         for (int i = 0; i < K; ++i) acc += (uint64_t)z[i] * ldc(bt, i);
-        yj = mont_reduce(acc, dm, ldc(a.to_p.dst_pinv, j));
+        yj = mont_step(acc, dm.p, ldc(a.to_p.dst_pinv, j));     // any 32-bit value is a valid operand of the Shoup product below
       } else {
 #pragma unroll
         for (int i = 0; i < K; ++i) {
           acc += (uint64_t)z[i] * ldc(bt, i);
           if ((i % kCadence) == kCadence - 2 && i + 1 < K) acc = reduce64(acc, dm);   // the term of d'_j came first
         }
-        yj = reduce64(acc, dm);
+        yj = reduce64_lazy(acc, dm);
       }
-      col[j * kThreads] = yj;
+      col[j * kThreads] = yj;                                     // made canonical by the exact path if it runs
       const Mod sm = ldc(a.to_q.src_mod, j);
       const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm.p);
       S2 += frac_est(z2, sm);
@@ -359,7 +363,13 @@ struct ScaleKernelR {
         }
       }
     }
-    auto exact_p = [&]() { return garner_gt_half(a.to_q, col, kThreads); };
+    auto exact_p = [&]() {
+      for (uint32_t j = 0; j < (uint32_t)KP; ++j) {
+        const Mod sm = ldc(a.to_q.src_mod, j);
+        col[j * kThreads] = reduce32(col[j * kThreads], sm);
+      }
+      return garner_gt_half(a.to_q, col, kThreads);
+    };
     const uint32_t v2 = bconv_round(S2, a.band, exact_p, a.fallback_counter);
 #pragma unroll
     for (int i = 0; i < K; ++i) {

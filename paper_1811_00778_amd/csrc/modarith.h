@@ -79,6 +79,11 @@ HCNN_HD uint32_t mont_reduce(uint64_t x, const Mod& m, uint32_t pinv) {
   const uint32_t u = (uint32_t)((x + (uint64_t)mm * m.p) >> 32);     // x + mm*p < 3*2^62 + 2^62
   return reduce32(u, m);
 }
+// The Montgomery step alone: x * 2^-32 mod p as a value below 2^32 (not reduced further), x < 3 * 2^62.
+HCNN_HD uint32_t mont_step(uint64_t x, uint32_t p, uint32_t pinv) {
+  const uint32_t mm = (uint32_t)x * pinv;
+  return (uint32_t)((x + (uint64_t)mm * p) >> 32);
+}
 // such a sum may hold kMontRoom products of two values below 2^30 (11 * 2^60 plus small terms < 3 * 2^62)
 constexpr uint32_t kMontRoom = 11;
 
