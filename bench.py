@@ -114,6 +114,11 @@ def time_primitives(n, k, torch, binding, gen, batch=64, reps=30):
         "keygen": (lambda: ctx.keygen(d_kr["s"], d_kr["a"], d_kr["e"], d_kr["a_evk"], d_kr["e_evk"]), None),
         "encrypt": (lambda: ctx.encrypt(pk, one(m), one(d_er["u"]), one(d_er["e1"]), one(d_er["e2"])),
                     lambda: ctx.encrypt(pk, m, d_er["u"], d_er["e1"], d_er["e2"])),
+        # randomness drawn on the device by the counter-based samplers, then Encrypt
+        "sample+encrypt": (lambda: ctx.encrypt(pk, one(m), ctx.sample_ternary(7, 1, 1), ctx.sample_gaussian(7, 2, 1),
+                                               ctx.sample_gaussian(7, 3, 1)),
+                           lambda: ctx.encrypt(pk, m, ctx.sample_ternary(7, 1, batch), ctx.sample_gaussian(7, 2, batch),
+                                               ctx.sample_gaussian(7, 3, batch))),
         "decrypt": (lambda: ctx.decrypt(d_kr["s"], cts[:1]), lambda: ctx.decrypt(d_kr["s"], cts)),
         "hadd": (lambda: ctx.ct_scalar_mac(cts, idx2, w2, 1, out=mac1), lambda: ctx.ct_scalar_mac(cts, idxa, wa, 1, out=macb)),
         "hmultplain": (lambda: ctx.ct_scalar_mac(cts, idx1, w1, 7, out=mac1), lambda: ctx.ct_scalar_mac(cts, idxb, wb, 7, out=macb)),

@@ -176,6 +176,26 @@ int hcnn_encrypt_wide(hcnn_ctx* ctx, const uint32_t* pk_dev, const uint64_t* m_d
 int hcnn_decrypt_wide(hcnn_ctx* ctx, const int32_t* sk_dev, const uint32_t* ct_dev, size_t n_ct,
                       uint64_t* m_out_dev);
 
+/* ---- deterministic sampling (test helpers) ------------------------------------------------
+ * The randomness of KeyGen and Encrypt (Sec. 2.1) always enters the library as explicit inputs.  These three calls
+ * produce such inputs on the device: every element is a fixed function of (seed, stream, element index), so the
+ * result does not depend on launch shapes and can be reproduced elsewhere.  Word source: Philox4x32 with 10 rounds
+ * (Salmon, Moraes, Dror, Shaw, SC'11), key = (seed low word, seed high word), counter = (index low word, index
+ * high word, low word of stream, kind * 2^24 + attempt); the four words of a call are used in order, then
+ * attempt + 1.  Element index = poly * n + coeff, and (poly * k + limb) * n + coeff for the uniform sampler.
+ *   hcnn_sample_ternary  (kind 1): out_dev int32[n_polys][n], uniform on {-1, 0, 1}: a word w is accepted unless
+ *                         w = 2^32 - 1; value = w mod 3 - 1.
+ *   hcnn_sample_gaussian (kind 2): out_dev int32[n_polys][n], round(N(0, 3.2^2)) with |value| <= 19 (larger values
+ *                         are redrawn): words in pairs (a, b); magnitude = number of thresholds T[0..19] that are
+ *                         <= a, T[v] = floor(2^32 * P(|X| <= v)); a pair with a >= T[19] is rejected; the sign is
+ *                         minus when the lowest bit of b is set.
+ *   hcnn_sample_uniform  (kind 3): out_dev uint32[n_polys][k][n], row l uniform in [0, q_l): a word w is accepted
+ *                         when w < q_l * floor(2^32 / q_l); value = w mod q_l.
+ * They return HCNN_OK, HCNN_ERR_NULL, HCNN_ERR_ARG (too many elements) or a HIP error code. */
+int hcnn_sample_ternary(hcnn_ctx* ctx, uint64_t seed, uint64_t stream, int32_t* out_dev, size_t n_polys);
+int hcnn_sample_gaussian(hcnn_ctx* ctx, uint64_t seed, uint64_t stream, int32_t* out_dev, size_t n_polys);
+int hcnn_sample_uniform(hcnn_ctx* ctx, uint64_t seed, uint64_t stream, uint32_t* out_dev, size_t n_polys);
+
 /* Noise read-out (the quantity behind the noise-budget figure of Sec. 5.5): with x = [c0 + c1*s]_q,
  * t*x = q*(m + t*a) + r for the centred remainder r = [t*x]_q; r/q is the invariant noise and Decrypt
  * returns m while |r/q| < 1/2.  bits_out_dev[i] = bit length of max_j |r_j| of ciphertext i (0 when every

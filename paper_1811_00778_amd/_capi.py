@@ -31,6 +31,9 @@ SIGNATURES = {
     "hcnn_encrypt_wide": [ptr, ptr, ptr, ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_decrypt_wide": [ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_noise_bits": [ptr, ptr, ptr, C.c_size_t, ptr],
+    "hcnn_sample_ternary": [ptr, C.c_uint64, C.c_uint64, ptr, C.c_size_t],
+    "hcnn_sample_gaussian": [ptr, C.c_uint64, C.c_uint64, ptr, C.c_size_t],
+    "hcnn_sample_uniform": [ptr, C.c_uint64, C.c_uint64, ptr, C.c_size_t],
     "hcnn_get_stat": [ptr, C.c_int, u64p],
     "hcnn_reset_stats": [ptr],
     "hcnn_set_option": [ptr, C.c_int, C.c_uint64],

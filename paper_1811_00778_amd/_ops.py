@@ -129,6 +129,25 @@ class OpsMixin:
                       n_ct, self._ptr(out))
         return out
 
+    # ---- deterministic sampling (inputs for keygen / encrypt, produced on the device)
+    def sample_ternary(self, seed, stream, n_polys):
+        """int32 [n_polys][n], uniform on {-1, 0, 1} (hcnn_sample_ternary)."""
+        out = self._empty((n_polys, self.n), "i32")
+        self.raw.call("hcnn_sample_ternary", int(seed), int(stream), self._ptr(out), n_polys)
+        return out
+
+    def sample_gaussian(self, seed, stream, n_polys):
+        """int32 [n_polys][n], rounded Gaussian sigma = 3.2 cut at 19 (hcnn_sample_gaussian)."""
+        out = self._empty((n_polys, self.n), "i32")
+        self.raw.call("hcnn_sample_gaussian", int(seed), int(stream), self._ptr(out), n_polys)
+        return out
+
+    def sample_uniform(self, seed, stream, n_polys):
+        """uint32 [n_polys][k][n], row l uniform in [0, q_l) (hcnn_sample_uniform)."""
+        out = self._empty((n_polys, self.k, self.n), "u32")
+        self.raw.call("hcnn_sample_uniform", int(seed), int(stream), self._ptr(out), n_polys)
+        return out
+
     def noise_bits(self, sk, cts):
         """Bit length of the largest centred remainder of t*(c0 + c1*s) mod q per ciphertext (hcnn_noise_bits);
         the noise budget is log2(q) - 1 - bits."""

@@ -879,6 +879,74 @@ struct DecRoundWideKernel {
   }
 };
 
+// ---------------------------------------------------------------- counter-based sampling
+// Every output element is a fixed function of (seed, stream, element index): the word source is Philox4x32 with
+// 10 rounds (Salmon et al., SC'11) keyed by the seed, with counter (index low, index high, stream, kind*2^24 +
+// attempt); a call gives four words, used in order, and a sampler that needs more moves on to attempt + 1.
+struct PhiloxWords { uint32_t w[4]; };
+HCNN_HD PhiloxWords philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t p0 = (uint64_t)c0 * 0xD2511F53u, p1 = (uint64_t)c2 * 0xCD9E8D57u;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  PhiloxWords r; r.w[0] = c0; r.w[1] = c1; r.w[2] = c2; r.w[3] = c3;
+  return r;
+}
+enum { kSampleTernary = 1, kSampleGaussian = 2, kSampleUniform = 3 };
+constexpr uint32_t kSampleMaxAttempts = 256;   // 1024 words: no sampler comes anywhere near (rejection odds <= 2^-29 per try,
+                                               // or 1 - 4p/2^32 for a prime p > 2^29 that is not close to 2^30)
+struct SampleArgs {
+  void* out;                 // int32 [count][n] (ternary, Gaussian) or uint32 [count][k][n] (uniform)
+  const Mod* mods;           // uniform: [k]
+  const uint32_t* gauss_t;   // Gaussian: 20 thresholds, T[v] = floor(2^32 * P(|X| <= v))
+  uint64_t seed, total;      // total elements
+  uint32_t stream, kind, k, n;
+};
+struct SampleKernel {
+  static constexpr int kThreads = kEwThreads;
+  static constexpr int kPhases = 1;
+  struct Regs {};
+  template <int PH>
+  HCNN_HD static void phase(const SampleArgs& a, unsigned bid, int tid, uint32_t*, Regs&) {
+    const uint64_t idx = (uint64_t)bid * kThreads + (uint64_t)tid;
+    if (idx >= a.total) return;
+    const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+    uint32_t p = 0, lim = 0;
+    if (a.kind == kSampleUniform) {
+      p = ldc(a.mods, (uint32_t)((idx / a.n) % a.k)).p;
+      lim = p * (uint32_t)(0x100000000ull / p);                    // accepted words: below the largest multiple of p
+    }
+    for (uint32_t attempt = 0; attempt < kSampleMaxAttempts; ++attempt) {
+      const PhiloxWords r = philox4x32_10((uint32_t)idx, (uint32_t)(idx >> 32), a.stream, (a.kind << 24) + attempt, k0, k1);
+      if (a.kind == kSampleGaussian) {
+        for (int s = 0; s < 4; s += 2) {
+          const uint32_t x = r.w[s], y = r.w[s + 1];
+          if (x >= ldc(a.gauss_t, 19)) continue;                    // beyond the cut: redraw
+          int32_t mag = 0;
+          for (uint32_t v = 0; v < 20; ++v) mag += ldc(a.gauss_t, v) <= x ? 1 : 0;
+          reinterpret_cast<int32_t*>(a.out)[idx] = (y & 1u) ? -mag : mag;
+          return;
+        }
+      } else {
+        for (int s = 0; s < 4; ++s) {
+          const uint32_t x = r.w[s];
+          if (a.kind == kSampleTernary) {
+            if (x == 0xFFFFFFFFu) continue;                         // 2^32 - 1 words split evenly over three values
+            reinterpret_cast<int32_t*>(a.out)[idx] = (int32_t)(x % 3u) - 1;
+          } else {
+            if (x >= lim) continue;
+            reinterpret_cast<uint32_t*>(a.out)[idx] = x % p;
+          }
+          return;
+        }
+      }
+    }
+    reinterpret_cast<uint32_t*>(a.out)[idx] = 0;                    // not reached in practice (see kSampleMaxAttempts)
+  }
+};
+
 // Noise read-out: x [count][k][n] (c0 + c1*s mod q) -> bits[count] = bit length of max_j |r_j|, r = [t*x]_q centred.
 // Exact: the residues of the non-negative remainder R = t*x mod q are turned into mixed-radix digits, R > (q-1)/2
 // is decided on the digits, |r| = R or q - R is rebuilt as a multiword integer by Horner's rule on the digits, and its

@@ -234,6 +234,7 @@ struct hcnn_ctx {
   uint32_t* d_tq_inv = nullptr;     // [kp] t * q^-1 mod p_j
   BConvDev ext{}, to_p{}, to_q{}, dec{};
   uint32_t neg_qinv_t = 0;
+  uint32_t* d_gauss_t = nullptr;    // thresholds of the Gaussian sampler (uploaded on first use)
   uint64_t* d_dec_wide = nullptr;   // plaintext modulus above 2^32: [k + 2] constants of the decrypt rounding
   unsigned long long* d_counters = nullptr;   // [2]
 
@@ -1052,6 +1053,42 @@ int hcnn_noise_bits(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n
     if ((e = run<NoiseKernel>(c, cc * bpp, NoiseKernel::lds_bytes(k), na))) return e;
   }
   return HCNN_OK;
+}
+
+// ---------------------------------------------------------------- sampling
+namespace {
+// T[v] = floor(2^32 * P(|X| <= v)), X = round(N(0, 3.2^2)), v = 0..19: a format constant of the samplers
+const uint32_t kGaussT[20] = {533280463u, 1549416568u, 2428136261u, 3117868636u, 3609276189u, 3927060812u, 4113592370u,
+                              4212972233u, 4261030606u, 4282124752u, 4290528529u, 4293567340u, 4294564687u, 4294861785u,
+                              4294942112u, 4294961823u, 4294966213u, 4294967101u, 4294967264u, 4294967291u};
+
+int sample_impl(hcnn_ctx* c, uint32_t kind, uint64_t seed, uint64_t stream, void* out, size_t count) {
+  if (!c) return HCNN_ERR_NULL;
+  if (count == 0) return HCNN_OK;
+  if (!out) return HCNN_ERR_NULL;
+  int e;
+  if (!c->d_gauss_t) {
+    std::vector<uint32_t> tab(kGaussT, kGaussT + 20);
+    if ((e = upload(c, tab, &c->d_gauss_t))) return e;
+  }
+  SampleArgs a;
+  a.out = out; a.mods = c->d_mods; a.gauss_t = c->d_gauss_t; a.seed = seed;
+  a.stream = (uint32_t)stream; a.kind = kind; a.k = c->k; a.n = c->n;
+  a.total = (uint64_t)count * c->n * (kind == kSampleUniform ? c->k : 1u);
+  const uint64_t blocks = (a.total + kEwThreads - 1) / kEwThreads;
+  if (blocks > 0x7fffffffull) return HCNN_ERR_ARG;
+  return run<SampleKernel>(c, (size_t)blocks, 0, a);
+}
+}  // namespace
+
+int hcnn_sample_ternary(hcnn_ctx* c, uint64_t seed, uint64_t stream, int32_t* out, size_t n_polys) {
+  return sample_impl(c, kSampleTernary, seed, stream, out, n_polys);
+}
+int hcnn_sample_gaussian(hcnn_ctx* c, uint64_t seed, uint64_t stream, int32_t* out, size_t n_polys) {
+  return sample_impl(c, kSampleGaussian, seed, stream, out, n_polys);
+}
+int hcnn_sample_uniform(hcnn_ctx* c, uint64_t seed, uint64_t stream, uint32_t* out, size_t n_polys) {
+  return sample_impl(c, kSampleUniform, seed, stream, out, n_polys);
 }
 
 // ---------------------------------------------------------------- diagnostics

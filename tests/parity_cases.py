@@ -418,3 +418,32 @@ def check_wide_plaintext(backend, n=1024, k=5, seed_id=1, force_exact=False):
     except _capi.HcnnError as exc:
         assert exc.code == _capi.ERR["T"]
     ctx.close()
+
+
+def check_samplers(backend, n, k, seed_id=1):
+    """hcnn_sample_* against the oracle's independent implementation of the same counter-based generator, element by
+    element; then keys and an encryption made from device samples only decrypt correctly."""
+    from oracle import rng
+    s = Setup(backend, n, k, seed_id=seed_id, with_keys=False)
+    ctx = s.ctx
+    seed, polys = 0x1234567887654321 + seed_id, 5
+    assert np.array_equal(backend.host(ctx.sample_ternary(seed, 1, polys)).view(np.int32), rng.sample_ternary(seed, 1, polys, n))
+    assert np.array_equal(backend.host(ctx.sample_gaussian(seed, 2, polys)).view(np.int32), rng.sample_gaussian(seed, 2, polys, n))
+    assert np.array_equal(backend.host(ctx.sample_uniform(seed, 3, polys)), rng.sample_uniform(seed, 3, polys, s.q, n))
+    # zero polynomials: nothing is written, nothing fails
+    assert backend.host(ctx.sample_ternary(seed, 1, 0)).size == 0
+    # the whole key and encryption flow from device samples
+    sk = ctx.sample_ternary(seed, 10, 1)
+    a = ctx.sample_uniform(seed, 11, 1)
+    e = ctx.sample_gaussian(seed, 12, 1)
+    a_evk = ctx.sample_uniform(seed, 13, k)
+    e_evk = ctx.sample_gaussian(seed, 14, k)
+    pk, evk = ctx.keygen(sk[0], a[0], e[0], a_evk, e_evk)
+    ctx.set_relin_key(evk)
+    m = s.rng.integers(0, s.t, size=(2, n), dtype=np.int64).astype(np.uint32)
+    cts = ctx.encrypt(pk, backend.dev(m), ctx.sample_ternary(seed, 20, 2), ctx.sample_gaussian(seed, 21, 2),
+                      ctx.sample_gaussian(seed, 22, 2))
+    assert np.array_equal(backend.host(ctx.decrypt(sk[0], cts)), m)
+    sk_h = backend.host(sk).view(np.int32)[0]
+    assert np.array_equal(fv.decrypt(s.octx, sk_h, backend.host(cts)[1]), m[1])
+    ctx.close()

@@ -92,6 +92,11 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_counter_based_samplers(backend):
+    pc.check_samplers(backend, 1024, 2)
+    pc.check_samplers(backend, 2048, 3, seed_id=2)
+
+
 def test_noise_read_out(backend):
     pc.check_noise_bits(backend, 1024, 2)
     pc.check_noise_bits(backend, 1024, 5)

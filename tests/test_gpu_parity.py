@@ -175,6 +175,12 @@ def test_two_contexts_on_two_streams(backend):
         s.ctx.close()
 
 
+def test_counter_based_samplers(backend):
+    say("samplers n=1024 k=2, n=8192 k=3")
+    pc.check_samplers(backend, 1024, 2)
+    pc.check_samplers(backend, 8192, 3, seed_id=2)
+
+
 def test_noise_read_out(backend):
     say("noise read-out n=1024 k=2, n=2048 k=5, n=8192 k=8")
     pc.check_noise_bits(backend, 1024, 2)
