@@ -15,6 +15,7 @@
 #include <cstddef>
 #include <cstdint>
 #include <cstdlib>
+#include <atomic>
 #include <cstring>
 #include <vector>
 
@@ -159,9 +160,15 @@ int launch(hcnn_stream_t s, size_t grid, size_t lds_bytes, const Args& a) {
   if (grid == 0) return 0;
   if (grid > 0x7fffffffull) return (int)hipErrorInvalidConfiguration;
   if (lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_entry<K, Args>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return (int)e;
+    // raised once per kernel and size (not on every launch, and so not while a caller records a graph after its
+    // warm-up call)
+    static std::atomic<size_t> allowed{0};
+    if (lds_bytes > allowed.load(std::memory_order_relaxed)) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_entry<K, Args>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return (int)e;
+      allowed.store(lds_bytes, std::memory_order_relaxed);
+    }
   }
   hipLaunchKernelGGL((kernel_entry<K, Args>), dim3((unsigned)grid), dim3(K::kThreads), lds_bytes, s, a);
   return (int)hipGetLastError();
