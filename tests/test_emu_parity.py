@@ -66,7 +66,8 @@ def test_square_relin_more_than_16_limbs(backend):
     pc.check_square_relin(backend, 1024, 17, n_random=1, n_genuine=1)
 
 
-@pytest.mark.parametrize("k,k_aux,big_t", [(8, 9, False), (16, 18, True), (24, 26, True)])
+@pytest.mark.parametrize("k,k_aux,big_t", [(8, 9, False), (11, 12, False), (12, 13, False), (10, 12, True), (11, 13, True),
+                                           (12, 14, True), (16, 18, True), (24, 26, True)])
 def test_square_relin_register_variants_of_standard_bases(backend, k, k_aux, big_t):
     # the basis sizes of the benchmark configurations, at a ring degree the oracle finishes quickly;
     # a larger plaintext modulus makes k' = k + 2 necessary already at n = 1024

@@ -74,6 +74,15 @@ def test_square_relin_chunked_ragged(backend):
     pc.check_square_relin(backend, 8192, 2, n_random=6, n_genuine=0, relin_order=2)            # key-major order
 
 
+def test_square_relin_largest_rings_residue_exact(backend):
+    """Whole squarings at n = 16384 and n = 32768 against the oracle residue by residue; two primes keep the
+    oracle's O(n^2) products to seconds (the deep configurations themselves are checked through decryption)."""
+    say("square_relin n=16384 k=2, n=32768 k=2 and k=6, every residue")
+    pc.check_square_relin(backend, 16384, 2, n_random=1, n_genuine=1, check_decrypt=False)   # a 60-bit q has no room for the result's noise
+    pc.check_square_relin(backend, 32768, 2, n_random=1, n_genuine=0)
+    pc.check_square_relin(backend, 32768, 6, n_random=1, n_genuine=0)
+
+
 def test_square_relin_exact_comparison_path(backend):
     say("square_relin forced exact comparison")
     pc.check_square_relin(backend, 1024, 2, force_exact=True)
@@ -85,7 +94,8 @@ def test_square_relin_more_than_16_limbs(backend):
     pc.check_square_relin(backend, 1024, 17, n_random=1, n_genuine=1)
 
 
-@pytest.mark.parametrize("k,k_aux,big_t", [(8, 9, False), (16, 18, True), (24, 26, True)])
+@pytest.mark.parametrize("k,k_aux,big_t", [(8, 9, False), (11, 12, False), (12, 13, False), (10, 12, True), (11, 13, True),
+                                           (12, 14, True), (16, 18, True), (24, 26, True)])
 def test_square_relin_register_variants_of_standard_bases(backend, k, k_aux, big_t):
     say("square_relin n=1024 k=%d k_aux=%d" % (k, k_aux))
     t = pc.slot_prime_above(1024, 1 << 22) if big_t else 65537
