@@ -447,3 +447,43 @@ def check_samplers(backend, n, k, seed_id=1):
     sk_h = backend.host(sk).view(np.int32)[0]
     assert np.array_equal(fv.decrypt(s.octx, sk_h, backend.host(cts)[1]), m[1])
     ctx.close()
+
+
+def check_random_sweep(backend, iterations, seed, sizes=(1024, 2048, 4096)):
+    """Seeded sweep over random parameter sets and shapes: ring degree, number of primes (1..7), plaintext modulus,
+    ambiguity band, batch size, gather geometry (groups, filters, terms) and weight bounds up to 2^31 - 1, with
+    extreme residues planted in the inputs; squaring, general product, scalar MAC and noise read-out must equal
+    the oracle on every draw."""
+    rng = np.random.default_rng(seed)
+    for it in range(iterations):
+        n = int(rng.choice(sizes))
+        k = int(rng.integers(1, 8))
+        t = int(rng.choice([65537, 2424833, 12289]))
+        if (t - 1) % (2 * n):
+            t = 65537
+        s = Setup(backend, n, k, t=t, seed_id=int(rng.integers(1, 1000)), stream=int(rng.integers(0, 100)))
+        s.ctx.set_relin_key(backend.dev(s.evk))
+        if rng.random() < 0.3:
+            s.ctx.set_ambiguity_band(int(2 ** rng.integers(7, 27)))
+        n_ct = int(rng.integers(1, 7))
+        cts = gen.uniform_residues(s.rng, s.q, n, lead=(n_ct, 2))
+        for l, p in enumerate(s.q):
+            pos = rng.integers(0, n, size=8)
+            cts[0, 0, l, pos] = rng.choice([0, 1, p - 1, (p - 1) // 2, (p + 1) // 2], size=8)
+        tag = (it, n, k, t, n_ct)
+        out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
+        for i in range(n_ct):
+            assert np.array_equal(out[i], fv.square_relin(s.octx, cts[i], s.evk)), ("square",) + tag
+        if n_ct >= 2:
+            prod = backend.host(s.ctx.ct_mul_relin(backend.dev(cts[:1]), backend.dev(cts[1:2])))
+            assert np.array_equal(prod[0], fv.hmult(s.octx, cts[0], cts[1], s.evk)), ("product",) + tag
+        G, F, T = int(rng.integers(1, 4)), int(rng.integers(1, 17)), int(rng.integers(1, 40))
+        bound = int(rng.choice([1, 7, 255, 2 ** 20, 2 ** 31 - 1]))
+        idx = rng.integers(0, n_ct, size=(G, T)).astype(np.uint32)
+        w = rng.integers(-bound, bound + 1, size=(G, F, T)).astype(np.int32)
+        mac = backend.host(s.ctx.ct_scalar_mac(backend.dev(cts), backend.dev(idx), backend.dev(w), bound))
+        g, f = int(rng.integers(0, G)), int(rng.integers(0, F))
+        assert np.array_equal(mac[f, g], fv.scalar_mac(s.octx, cts, idx[g], w[g, f])), ("mac", G, F, T, bound) + tag
+        bits = backend.host(s.ctx.noise_bits(backend.dev(s.kr["s"]), backend.dev(cts[:1])))
+        assert int(bits[0]) == fv.noise_bits(s.octx, s.kr["s"], cts[0]), ("noise",) + tag
+        s.ctx.close()

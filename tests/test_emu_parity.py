@@ -93,6 +93,10 @@ def test_conv_square_layer(backend):
     pc.check_conv_layer_small(backend)
 
 
+def test_random_parameter_sweep(backend):
+    pc.check_random_sweep(backend, 6, seed=7, sizes=(1024,))
+
+
 def test_counter_based_samplers(backend):
     pc.check_samplers(backend, 1024, 2)
     pc.check_samplers(backend, 2048, 3, seed_id=2)

@@ -191,6 +191,11 @@ def test_two_contexts_on_two_streams(backend):
         s.ctx.close()
 
 
+def test_random_parameter_sweep(backend):
+    say("seeded sweep over 60 random parameter sets and shapes")
+    pc.check_random_sweep(backend, 60, seed=20261127)
+
+
 def test_counter_based_samplers(backend):
     say("samplers n=1024 k=2, n=8192 k=3")
     pc.check_samplers(backend, 1024, 2)
