@@ -333,11 +333,16 @@ struct NttInv {
 #pragma unroll
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
+            // A product that the next level subtracts (its position is a right operand there) is kept
+            // negated mod 2^32: the difference then is one three-operand addition.
+            const bool y_neg = l < NS - 1 && (x & (half >> 1)) != 0;    // v[ib] was stored negated by level l + 1
+            const bool out_neg = l > 0 && (h & 1) != 0;                 // v[ib] is a right operand of level l - 1
             const uint32_t X = v[ia], Y = v[ib];
-            const uint32_t S = X + Y;                                   // [0, 4p)
-            const uint32_t D = X + two_p - Y;                           // (0, 4p)
+            const uint32_t S = y_neg ? X - Y : X + Y;                   // [0, 4p)
+            const uint32_t D = y_neg ? X + two_p + Y : X + two_p - Y;   // (0, 4p)
             v[ia] = top ? shoup_lazy(S, nv.w, nv.ws, p) : csub(S, two_p);
-            v[ib] = shoup_lazy(D, w.w, w.ws, p);                        // [0, 2p)
+            v[ib] = out_neg ? mulhi32(D, w.ws) * p - D * w.w            // -(D * w mod p) - {0, p}  (mod 2^32)
+                            : shoup_lazy(D, w.w, w.ws, p);              // [0, 2p)
           }
         }
       }
