@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 ALU_PEAK_TOPS = 39.3           # 256 CU x 64 lanes x 2.4 GHz 32-bit integer VALU instructions / s
+RELIN_FUSED_TRAFFIC_RATIO = 1.703   # counted / algorithmic bytes of the one-kernel relinearisation at batch 64 (profiles/)
 
 
 def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
@@ -292,7 +293,7 @@ def main():
         dom = max(kernels, key=lambda kname: kernels[kname]["total_ms"])
         kd = kernels[dom]
         avg_s = kd["total_ms"] / kd["launches"] * 1e-3
-        if dom in ("ntt_fwd", "ntt_inv"):
+        if dom in ("ntt_fwd", "ntt_inv", "relin_fused"):
             # The transform is bound by integer VALU issue, not by HBM: a lazy butterfly needs 8 VALU
             # instructions (3 multiplies, a 2-instruction conditional subtract, 3 add/sub), i.e.
             # 8 * (n/2) * log2(n) per row = 6.5 instructions per byte moved, above the chip's balance of
@@ -302,7 +303,7 @@ def main():
             instr_per_launch = rows_per_launch * butterflies * 8
             ach = instr_per_launch / avg_s / 1e12
             # Algorithmic HBM bytes of the class's three launches per step (a plain row is read and written once;
-            # the k transforms of a digit row share one read, the three tensor components of a (ciphertext, limb)
+            # the three tensor components of a (ciphertext, limb)
             # pair share two reads, an adding store reads its addend too), and the bytes that the HBM counters
             # attribute to them: ratios of counted to algorithmic bytes per kernel, measured with rocprofv3
             # FETCH_SIZE / WRITE_SIZE on this workload (profiles/bench_primitive8192_hbm_counters.md).
@@ -310,13 +311,16 @@ def main():
             row4 = 4 * n
             if dom == "ntt_fwd":
                 parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
-                         (n_ct * 2 * L_ * 2 * row4, 1.077),                                 # extended operands
-                         (n_ct * k * k * row4 + n_ct * k * row4, 1.030)]                    # digit load
-            else:
+                         (n_ct * 2 * L_ * 2 * row4, 1.077)]                                 # extended operands
+            elif dom == "ntt_inv":
                 parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
                          (n_ct * 3 * L_ * row4 + n_ct * 2 * L_ * row4, 1.134),              # tensor-forming load
                          (n_ct * 2 * k * 3 * row4, 1.008)]                                  # adding store
-            per_step_launches = 3
+            else:
+                # relinearisation in one kernel: reads y (3k rows per ciphertext), writes the result (2k rows);
+                # the key comes from L2.  `blocks` of this class counts transformed rows (k + 2 per workgroup).
+                parts = [(n_ct * 5 * k * row4, RELIN_FUSED_TRAFFIC_RATIO)]
+            per_step_launches = 1 if dom == "relin_fused" else (3 if dom == "ntt_inv" else 2)
             bytes_per_launch = sum(b for b, _ in parts) / per_step_launches
             traffic = sum(b * r for b, r in parts) / per_step_launches
             roofline = dict(kernel=dom, bound="alu", achieved=round(ach, 2), peak=ALU_PEAK_TOPS,

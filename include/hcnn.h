@@ -225,9 +225,15 @@ enum {
   HCNN_OPT_SQUARE_CHUNK = 1,    /* ciphertexts per internal batch of hcnn_ct_square_relin;
                                    0 = choose from the scratch budget */
   HCNN_OPT_PROFILE = 2,         /* non-zero: record a HIP event pair around every kernel launch */
-  HCNN_OPT_RELIN_ORDER = 3      /* workgroup order of the evaluation-key inner product: 0 = chosen from
+  HCNN_OPT_RELIN_ORDER = 3,     /* workgroup order of the evaluation-key inner product: 0 = chosen from
                                    the key size (default), 1 = ciphertext-major, 2 = key-major (needs
                                    n >= 8192).  Same results either way; for tests and tuning. */
+  HCNN_OPT_RELIN_SPLIT = 4      /* relinearisation (HMult step 3) of rings n <= 8192: 0 (default) = one kernel
+                                   (digit transforms, inner product with the key and inverse transforms
+                                   without leaving the registers) for as many ciphertexts of a batch as fill
+                                   whole rounds of its workgroups on the device, the three separate kernels
+                                   for the rest and for small batches; 1 = always the separate kernels;
+                                   2 = always the one kernel.  Same results either way; for tests and tuning. */
 };
 int hcnn_set_option(hcnn_ctx* ctx, int which, uint64_t value);
 
@@ -235,7 +241,8 @@ int hcnn_set_option(hcnn_ctx* ctx, int which, uint64_t value);
  * path (the classes follow the steps of HMult in Sec. 2.1 and the layer sum of Sec. 4.3).
  * `blocks` is the number of workgroups launched: one (polynomial, limb) row of n residues per
  * workgroup for the two NTT classes, 256 coefficient positions (1024 for RELIN_MAC and
- * SCALAR_MAC) per workgroup for the others.
+ * SCALAR_MAC) per workgroup for the others; for RELIN_FUSED it is the number of rows the launch
+ * transforms (k forward + 2 inverse per workgroup).
  * hcnn_profile_read synchronises the stream; hcnn_reset_stats clears the accumulators. */
 enum {
   HCNN_PROF_NTT_FWD = 0,
@@ -248,7 +255,10 @@ enum {
   HCNN_PROF_RELIN_ADD = 7,   /* final addition: fused into NTT_INV, stays 0           */
   HCNN_PROF_SCALAR_MAC = 8,
   HCNN_PROF_OTHER = 9,
-  HCNN_PROF_COUNT = 10
+  HCNN_PROF_RELIN_FUSED = 10, /* relinearisation in one kernel (digit transforms, inner product, inverse
+                                 transforms and final addition); DIGIT-side NTT_FWD rows, RELIN_MAC and the
+                                 adding NTT_INV rows are then not launched */
+  HCNN_PROF_COUNT = 11
 };
 int hcnn_profile_read(hcnn_ctx* ctx, int kernel_class, uint64_t* launches, uint64_t* blocks,
                       double* total_ms);

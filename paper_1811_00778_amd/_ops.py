@@ -182,6 +182,10 @@ class OpsMixin:
     def set_relin_order(self, order):
         self.raw.set_option(_capi.OPT_RELIN_ORDER, order)
 
+    def set_relin_split(self, mode):
+        """Form of the relinearisation: 0 chosen per batch, 1 always three separate kernels, 2 always one kernel."""
+        self.raw.set_option(_capi.OPT_RELIN_SPLIT, int(mode))
+
     def set_square_chunk(self, chunk):
         self.raw.set_option(_capi.OPT_SQUARE_CHUNK, chunk)
 

@@ -247,7 +247,9 @@ struct hcnn_ctx {
   uint32_t band = 128;
   uint64_t square_chunk = 0;
   uint64_t relin_order = 0;   // 0 = by key size, 1 = ciphertext-major, 2 = key-major
+  uint64_t relin_split = 0;   // 0 = one relinearisation kernel for whole rounds of its workgroups, 1 = never, 2 = always (n <= 8192)
   size_t max_lds = 0;
+  uint32_t compute_units = 256;
 
   // optional per-kernel timing (HCNN_OPT_PROFILE): an event pair around every launch
   struct Pending { int cls; uint64_t blocks; hcnn_event_t start, stop; };
@@ -283,6 +285,7 @@ template <int A, int B> struct KernelClass<ExtKernelT<A, B>> { static constexpr 
 template <int A, int B> struct KernelClass<ScaleKernelR<A, B>> { static constexpr int id = HCNN_PROF_SCALE; };
 template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
 template <int A> struct KernelClass<RelinMacKernel<A>> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
+template <int A, int B, int C> struct KernelClass<RelinFused<A, B, C>> { static constexpr int id = HCNN_PROF_RELIN_FUSED; };
 template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 template <int F> struct KernelClass<MacKernelDirect<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 
@@ -685,6 +688,7 @@ int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, u
   if (k_aux) c->p.assign(p, p + k_aux);
   c->stream = (hcnn_stream_t)hip_stream;
   c->max_lds = max_lds_bytes();
+  c->compute_units = compute_unit_count();
   if (c->max_lds < (size_t)(n + n / 32) * 4) {
     delete c;
     return HCNN_ERR_NODEVICE;
@@ -780,6 +784,14 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
 }
 
 // HMult of Sec. 2.1 on n_ct pairs (a_i, b_i); b == nullptr squares a (HSquare).
+// Workgroups of the one-kernel relinearisation that the device holds at a time: its register use allows
+// 8 waves per compute unit at n = 8192 (213 registers, 4 waves per workgroup) and 16 below (128 registers).
+static size_t relin_fused_slots(const hcnn_ctx* c) {
+  const size_t waves_per_wg = std::max<size_t>(1, ((size_t)1 << c->logn) / (c->logn >= 13 ? 32 : 16) / 64);
+  const size_t waves_per_cu = c->logn >= 13 ? 8 : 16;
+  return (size_t)c->compute_units * (waves_per_cu / waves_per_wg);
+}
+
 static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b, size_t n_ct, uint32_t* out) {
   if (!c) return HCNN_ERR_NULL;
   if (n_ct == 0) return HCNN_OK;
@@ -790,7 +802,17 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   const uint32_t k = c->k, kp = c->kp, L = k + kp, n = c->n;
   const size_t rn = n;
   const size_t ext_rows = in_b ? 4 * (size_t)L : 2 * (size_t)L;
-  const size_t words_per_ct = (ext_rows + 3 * L + 3 * k + (size_t)k * k + 2 * k) * rn;
+  // n <= 8192: relinearisation runs as one kernel that needs no buffers for the transformed digits and the sums.
+  // (At n = 16384 a workgroup of that kernel would fill a compute unit alone; measured at half the speed.)
+  // Its workgroups are long (k + 2 transforms each), so it only takes whole rounds of resident workgroups; what is
+  // left of a batch (all of a small batch) goes through the three separate kernels, which spread k^2 rows per
+  // ciphertext over the chip.
+  const bool fused = c->relin_split != 1 && c->logn <= 13;
+  // (the k workgroups of a ciphertext share a die, for its L2: a round is counted per die)
+  const size_t fused_round = fused ? relin_fused_slots(c) / kXcds / k * kXcds : 0;   // ciphertexts per round (0: never)
+  const size_t words_main = (ext_rows + 3 * L + 3 * k) * rn;
+  const size_t words_split = ((size_t)k * k + 2 * k) * rn;
+  const size_t words_per_ct = words_main + words_split;
   size_t C = c->square_chunk;
   if (C == 0) {
     const size_t budget = (size_t)6 << 30;   // 6 GiB of scratch (of 288 GB): enough rows per launch at every n
@@ -801,14 +823,16 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   if (C > n_ct) C = n_ct;
   const size_t need_lds_scale = ScaleKernel::lds_bytes(k, kp);
   if (need_lds_scale > c->max_lds) return HCNN_ERR_NODEVICE;
-  int e = ensure_scratch(c, C * words_per_ct * 4);
+  // ciphertexts of one internal batch that can take the separate kernels
+  const size_t C_split = (fused && fused_round) ? std::min(C, fused_round) : C;
+  int e = ensure_scratch(c, (C * words_main + C_split * words_split) * 4);
   if (e) return e;
   uint32_t* ext = c->scratch;
   uint32_t* ext_b = ext + C * 2 * L * rn;                 // used only by the two-operand product
   uint32_t* d = ext + C * ext_rows * rn;
   uint32_t* y = d + C * 3 * L * rn;
   uint32_t* dig = y + C * 3 * k * rn;
-  uint32_t* acc = dig + C * k * k * rn;
+  uint32_t* acc = dig + C_split * k * k * rn;
   const size_t ct_words = (size_t)2 * k * rn;
   const size_t bpp = n / kEwThreads;                 // blocks per polynomial, 1 coefficient / thread
   const size_t bpr = n / (kEwThreads * kEwVec);      // blocks per row, 4 coefficients / thread
@@ -837,8 +861,38 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
     sa.band = c->band; sa.fallback_counter = c->d_counters;
     if ((e = scale_dispatch(c, cc * 3 * bpp, sa))) return e;
+    // 6-8 in one kernel for whole rounds of its workgroups (a row and its two 64-bit sums stay in registers)
+    size_t nf = 0;
+    if (fused && fused_round) {
+      nf = cc / fused_round * fused_round;
+      // a last round joins when it is at least 3/8 full (3/4 if it is the only one): measured break-even points
+      const size_t rest = cc - nf;
+      if (nf ? rest * 8 >= fused_round * 3 : rest * 4 >= fused_round * 3) nf = cc;
+      if (c->relin_split == 2) nf = cc;
+    }
+    if (nf) {
+      RelinFusedArgs fa{y, c->d_evk_hat, out + c0 * ct_words, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, (uint32_t)(nf * k)};
+      const size_t grid = ntt_grouped_grid(nf * k, k), rows = nf * k * (k + 2);
+#define HCNN_FUSED(LOGN, LOGR)                                                                                      \
+  (k <= 8 ? run<RelinFused<LOGN, LOGR, kNttFusedMac>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows)             \
+          : k <= 15 ? run<RelinFused<LOGN, LOGR, kNttFusedMac15>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows) \
+                    : run<RelinFused<LOGN, LOGR, kNttFusedMacAny>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows))
+      switch (c->logn) {
+        case 10: e = HCNN_FUSED(10, 4); break;
+        case 11: e = HCNN_FUSED(11, 4); break;
+        case 12: e = HCNN_FUSED(12, 4); break;
+        case 13: e = HCNN_FUSED(13, 5); break;
+        default: e = HCNN_ERR_N; break;
+      }
+#undef HCNN_FUSED
+      if (e) return e;
+    }
+    const size_t ns = cc - nf;                                // ciphertexts left for the separate kernels
+    if (ns == 0) continue;
+    const uint32_t* y_s = y + nf * 3 * k * rn;
+    uint32_t* out_s = out + (c0 + nf) * ct_words;
     // 6. RNS digits of y2, each reduced modulo every q_j while loading, transformed
-    if ((e = ntt_dense(c, y, dig, cc * k * k, k, false, kNttLoadDigit))) return e;
+    if ((e = ntt_dense(c, y_s, dig, ns * k * k, k, false, kNttLoadDigit))) return e;
     // 7. inner product with the evaluation key
     RelinMacArgs ra;
     ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
@@ -848,17 +902,17 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     if (c->relin_order == 2 && bpr % kXcds == 0) ra.key_major = 1;
     // groups of kRelinCts ciphertexts share their loads of the key; the remainder goes one by one
     constexpr int kRelinCts = 4;
-    const size_t full = cc / kRelinCts;
+    const size_t full = ns / kRelinCts;
     if (full) {
       ra.n_grp = (uint32_t)full; ra.ct_base = 0;
       if ((e = run<RelinMacKernel<kRelinCts>>(c, full * k * bpr, 0, ra))) return e;
     }
-    if (cc % kRelinCts) {
-      ra.n_grp = (uint32_t)(cc % kRelinCts); ra.ct_base = (uint32_t)(full * kRelinCts);
-      if ((e = run<RelinMacKernel<1>>(c, (cc % kRelinCts) * k * bpr, 0, ra))) return e;
+    if (ns % kRelinCts) {
+      ra.n_grp = (uint32_t)(ns % kRelinCts); ra.ct_base = (uint32_t)(full * kRelinCts);
+      if ((e = run<RelinMacKernel<1>>(c, (ns % kRelinCts) * k * bpr, 0, ra))) return e;
     }
     // 8. c'_b = y_b + sum_i evk[i][b] * digit_i : inverse transform with the addition on the way out
-    if ((e = ntt_dense(c, acc, out + c0 * ct_words, cc * 2 * k, k, true, kNttStoreAdd, y))) return e;
+    if ((e = ntt_dense(c, acc, out_s, ns * 2 * k, k, true, kNttStoreAdd, y_s))) return e;
   }
   return HCNN_OK;
 }
@@ -1142,6 +1196,10 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
     case HCNN_OPT_RELIN_ORDER:
       if (value > 2) return HCNN_ERR_ARG;
       c->relin_order = value;
+      return HCNN_OK;
+    case HCNN_OPT_RELIN_SPLIT:
+      if (value > 2) return HCNN_ERR_ARG;
+      c->relin_split = value;
       return HCNN_OK;
   }
   return HCNN_ERR_ARG;

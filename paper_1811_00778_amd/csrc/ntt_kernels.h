@@ -51,8 +51,23 @@ struct NttLimb {
 //                   its Montgomery reduction)
 // The tensor-forming loads also leave their output lazily reduced, in [0, 2p): its only reader multiplies it
 // by a constant with Shoup's method, which takes any 32-bit operand.
+//   kNttFusedMac    forward only, inside RelinFused: workgroup (ct, j) transforms digit `iter` of y2 modulo q_j
+//                   (loaded like kNttLoadDigit) and, instead of storing, adds its products with the two key
+//                   rows evk^[iter][0][j], evk^[iter][1][j] (`aux`) to 64-bit sums held in registers
+//   kNttFromRegs0/1 inverse only, inside RelinFused: the input is the register-held sum of component 0 / 1;
+//                   the output adds y row (ct, b, j) (`aux`) like kNttStoreAdd and goes to out row (ct, b, j)
 enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4,
-             kNttStoreLazy = 5 };
+             kNttStoreLazy = 5, kNttFusedMac = 6, kNttFromRegs0 = 7, kNttFromRegs1 = 8,
+             kNttFusedMac15 = 9, kNttFusedMacAny = 10 };   // the fused inner product for k <= 8, k <= 15, any k
+
+// Per-thread state of RelinFused: the iteration (digit) and the two inner-product sums of every residue the
+// thread holds after the last forward pass.
+template <int R>
+struct RelinRegs {
+  uint32_t iter;
+  uint64_t s0[R], s1[R];
+};
+struct NoRegs {};
 
 struct NttArgs {
   const uint32_t* in;
@@ -112,20 +127,24 @@ struct NttGeom {
 // ------------------------------------------------------------------------- forward
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttFwd {
-  static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy, "forward NTT: plain, digit load or lazy store");
+  static constexpr bool kFused = IO == kNttFusedMac || IO == kNttFusedMac15 || IO == kNttFusedMacAny;
+  static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy || kFused,
+                "forward NTT: plain, digit load, lazy store or fused inner product");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
-  struct Regs {};
+  static constexpr bool kDigitIn = IO == kNttLoadDigit || kFused;
+  using Regs = std::conditional_t<kFused, RelinRegs<G::R>, NoRegs>;
 
   template <int PH>
-  HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+  HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
     constexpr int N = G::N, R = G::R;
     constexpr int S0 = G::s0(PH), NS = G::ns(PH), NET = 1 << NS, C = R / NET;
     constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
     constexpr bool kFirst = PH == 0, kLast = PH == kPhases - 1;
+    if constexpr (kFused) tid = opaque(tid);
 
-    if constexpr (IO == kNttLoadDigit) {
+    if constexpr (kDigitIn) {
       bid = ntt_grouped_index(bid, a.limb_cycle);      // the k transforms of one digit row share a die
       if (bid >= a.n_rows) return;
     }
@@ -134,13 +153,23 @@ struct NttFwd {
     const uint32_t p = L.m.p, two_p = 2 * L.m.p;
     const ShoupConst* tw = a.tw + (size_t)limb * N;
     const uint32_t* gin;
-    if constexpr (IO == kNttLoadDigit) {
+    uint32_t* gout = nullptr;
+    const uint32_t* key0 = nullptr;       // kNttFusedMac: evk^[iter][0][j]; component 1 lies k rows further
+    if constexpr (kFused) {
+      const uint32_t kk = a.limb_cycle;                // rows are (ct, j)
+      gin = a.in + ((size_t)(bid / kk) * 3 * kk + 2 * kk + regs.iter) * N;
+      key0 = a.aux + ((size_t)regs.iter * 2 * kk + limb) * N;
+      if (kFirst && regs.iter == 0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) { regs.s0[r] = 0; regs.s1[r] = 0; }
+      }
+    } else if constexpr (IO == kNttLoadDigit) {
       const uint32_t kk = a.limb_cycle;
       gin = a.in + ((size_t)(bid / (kk * kk)) * 3 * kk + 2 * kk + (bid / kk) % kk) * N;
     } else {
       gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
     }
-    uint32_t* gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+    if constexpr (!kFused) gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
 
 #pragma unroll
     for (int c = 0; c < C; ++c) {
@@ -171,7 +200,32 @@ struct NttFwd {
           }
         }
       }
-      if constexpr (kLast && NET >= 4) {
+      if constexpr (kLast && kFused) {
+        // The transformed digit times the key rows (below p < 2^30), added to the 64-bit sums.  With the digit only
+        // brought into [0, 2p), 8 products stay below 16 p^2 < 2^64 (kNttFusedMac, k <= 8); with the digit made
+        // canonical, 15 products and a residue do (kNttFusedMac15, k <= 15), and kNttFusedMacAny folds the sums
+        // before digits 15, 30, ...
+        const uint32_t* key1 = key0 + (size_t)a.limb_cycle * N;
+        uint32_t e0[NET], e1[NET];
+#pragma unroll
+        for (int e = 0; e < NET; ++e) { e0[e] = key0[base + (uint32_t)e]; e1[e] = key1[base + (uint32_t)e]; }
+        if constexpr (IO == kNttFusedMacAny) {
+          if (regs.iter != 0 && regs.iter % 15 == 0) {
+#pragma unroll
+            for (int e = 0; e < NET; ++e) {
+              regs.s0[c * NET + e] = reduce64(regs.s0[c * NET + e], L.m);
+              regs.s1[c * NET + e] = reduce64(regs.s1[c * NET + e], L.m);
+            }
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < NET; ++e) {
+          uint32_t d = csub(v[e], two_p);
+          if constexpr (IO != kNttFusedMac) d = csub(d, p);
+          regs.s0[c * NET + e] += (uint64_t)d * e0[e];
+          regs.s1[c * NET + e] += (uint64_t)d * e1[e];
+        }
+      } else if constexpr (kLast && NET >= 4) {
         // TLAST == 1: the network is NET consecutive coefficients -> 16-byte stores
         U4* g4 = reinterpret_cast<U4*>(gout + base);
 #pragma unroll
@@ -201,15 +255,16 @@ struct NttFwd {
 // ------------------------------------------------------------------------- inverse
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttInv {
-  static_assert(IO == kNttPlain || IO == kNttLoadTensor || IO == kNttStoreAdd || IO == kNttLoadTensorMul,
-                "inverse NTT io mode");
+  static_assert(IO == kNttPlain || IO == kNttLoadTensor || IO == kNttStoreAdd || IO == kNttLoadTensorMul ||
+                IO == kNttFromRegs0 || IO == kNttFromRegs1, "inverse NTT io mode");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
-  struct Regs {};
+  static constexpr bool kFromRegs = IO == kNttFromRegs0 || IO == kNttFromRegs1;
+  using Regs = std::conditional_t<kFromRegs, RelinRegs<G::R>, NoRegs>;
 
   template <int PHI>
-  HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs&) {
+  HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
     constexpr int PH = kPhases - 1 - PHI;   // mirrors forward pass PH
     constexpr int N = G::N, R = G::R;
     constexpr int S0 = G::s0(PH), NS = G::ns(PH), NET = 1 << NS, C = R / NET;
@@ -224,11 +279,15 @@ struct NttInv {
       bid = ((unit / LL) * 3 + b) * LL + unit % LL;            // row (ct, b, l)
       if (unit >= a.n_rows / 3) return;
     }
+    if constexpr (kFromRegs) {
+      bid = ntt_grouped_index(bid, a.limb_cycle);      // the same workgroup -> (ct, j) map as kNttFusedMac
+      if (bid >= a.n_rows) return;
+    }
     const uint32_t limb = a.limb_base + bid % a.limb_cycle;
     const NttLimb L = ldc(a.limbs, limb);
     const uint32_t p = L.m.p, two_p = 2 * L.m.p;
     const ShoupConst* tw = a.tw + (size_t)limb * N;
-    const uint32_t* gin;
+    const uint32_t* gin = nullptr;
     const uint32_t* gin2 = nullptr;       // kNttLoadTensor: the c1^ row
     uint32_t comp = 0;                    // kNttLoadTensor: tensor component b
     const uint32_t* gmul0 = nullptr;      // kNttLoadTensorMul: rows c0^, c1^ of the first operand and
@@ -249,11 +308,18 @@ struct NttInv {
       // b = 0: c0*c0' ; b = 2: c1*c1' ; b = 1: c0*c1' + c1*c0'
       gin = gmul0 + (comp == 2 ? (size_t)LL * N : 0);
       gin2 = gmul1 + (comp == 0 ? 0 : (size_t)LL * N);
-    } else {
+    } else if constexpr (!kFromRegs) {
       gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
     }
-    uint32_t* gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+    uint32_t* gout;
     const uint32_t* gaux = nullptr;
+    if constexpr (kFromRegs) {
+      const uint32_t kk = a.limb_cycle, ct = bid / kk, b = IO == kNttFromRegs1 ? 1u : 0u;
+      gout = a.out + ((size_t)(ct * 2 + b) * kk + bid % kk) * N;
+      gaux = a.aux + ((size_t)(ct * 3 + b) * kk + bid % kk) * N;
+    } else {
+      gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+    }
     if constexpr (IO == kNttStoreAdd) {
       const uint32_t kk = a.limb_cycle, grp = bid / kk;
       gaux = a.aux + ((size_t)(grp / 2) * 3 * kk + (size_t)(grp % 2) * kk + bid % kk) * N;
@@ -266,7 +332,12 @@ struct NttInv {
       const uint32_t base = i * (uint32_t)(NET * TLAST) + o;
       const uint32_t sbase = lds_swz(base);
       uint32_t v[NET];
-      if constexpr (kFirst && NET >= 4) {
+      if constexpr (kFirst && kFromRegs) {
+        // the sums sit where the last forward pass left its residues, which is where this pass takes them
+#pragma unroll
+        for (int e = 0; e < NET; ++e)
+          v[e] = reduce64(IO == kNttFromRegs1 ? regs.s1[c * NET + e] : regs.s0[c * NET + e], L.m);
+      } else if constexpr (kFirst && NET >= 4) {
         // TLAST == 1: NET consecutive coefficients -> 16-byte loads
         const U4* g4 = reinterpret_cast<const U4*>(gin + base);
 #pragma unroll
@@ -346,7 +417,7 @@ struct NttInv {
           }
         }
       }
-      if constexpr (kLast && IO == kNttStoreAdd) {
+      if constexpr (kLast && (IO == kNttStoreAdd || kFromRegs)) {
         // all loads of the addend before the first store (the compiler must assume the buffers alias)
         uint32_t addend[NET];
 #pragma unroll
@@ -361,6 +432,50 @@ struct NttInv {
 #pragma unroll
         for (int e = 0; e < NET; ++e) lds[lds_elem<LOG_TLAST>(sbase, e)] = v[e];
       }
+    }
+  }
+};
+
+// ------------------------------------------------------------------------- relinearisation in one kernel
+// Workgroup (ct, j): for every digit i of y2[ct] -- forward transform modulo q_j, products with the two key rows
+// added to register-held sums -- then the two sums go back through the inverse transform and leave as
+// c'_b = y_b + sum_i evk[i][b] * digit_i (HMult step 3).  Neither the transformed digits nor the sums touch memory.
+struct RelinFusedArgs {
+  const uint32_t* y;        // [n_ct][3][k][n]
+  const uint32_t* evk;      // [k][2][k][n], transformed
+  uint32_t* out;            // [n_ct][2][k][n]
+  const ShoupConst* tw_fwd;
+  const ShoupConst* tw_inv;
+  const NttLimb* limbs;
+  uint32_t k;
+  uint32_t n_rows;          // n_ct * k
+};
+
+template <int LOGN, int LOGR, int MAC = kNttFusedMacAny>
+struct RelinFused {
+  using G = NttGeom<LOGN, LOGR>;
+  using Fwd = NttFwd<LOGN, LOGR, MAC>;
+  using Inv0 = NttInv<LOGN, LOGR, kNttFromRegs0>;
+  using Inv1 = NttInv<LOGN, LOGR, kNttFromRegs1>;
+  static constexpr int P = G::kPhases;
+  static constexpr int kThreads = G::kThreads;
+  static constexpr int kLoopPhases = P;
+  static constexpr int kMinWavesPerSimd = G::kThreads / 256 * 2 > 0 ? G::kThreads / 256 * 2 : 1;   // room for two workgroups per compute unit
+  static constexpr int kPhases = 3 * P;
+  using Regs = RelinRegs<G::R>;
+  HCNN_HD static uint32_t loop_count(const RelinFusedArgs& a) { return a.k; }
+
+  template <int PH>
+  HCNN_HD static void phase(const RelinFusedArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
+    NttArgs na{};
+    na.limbs = a.limbs; na.limb_cycle = a.k; na.limb_base = 0; na.n_rows = a.n_rows;
+    if constexpr (PH < P) {
+      na.in = a.y; na.aux = a.evk; na.tw = a.tw_fwd;
+      Fwd::template phase<PH>(na, bid, tid, lds, regs);
+    } else {
+      na.aux = a.y; na.out = a.out; na.tw = a.tw_inv;
+      if constexpr (PH < 2 * P) Inv0::template phase<PH - P>(na, bid, tid, lds, regs);
+      else Inv1::template phase<PH - 2 * P>(na, bid, tid, lds, regs);
     }
   }
 };

@@ -5,6 +5,9 @@
 //   kPhases                       number of barrier-separated phases
 //   struct Regs                   per-thread state that lives across barriers
 //   template<int PH> phase(args, block, tid, lds, regs)
+// and, optionally, a repeated prefix:
+//   kLoopPhases, loop_count(args) phases [0, kLoopPhases) run loop_count times (Regs::iter = the iteration, a
+//                                 barrier after every one of them), then the remaining phases once
 // The HIP build runs the phases of one workgroup inside one __global__ function
 // with __syncthreads() between phases.  The HCNN_HOSTEMU build (used only by the
 // CPU test-suite to check kernel indexing and arithmetic before anything touches
@@ -17,6 +20,7 @@
 #include <cstdlib>
 #include <atomic>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #ifdef HCNN_HOSTEMU
@@ -40,6 +44,16 @@ struct alignas(16) U4 { uint32_t x, y, z, w; };
 #else
 typedef uint4 U4;
 #endif
+
+// opaque(x): x again, but as a value the compiler cannot trace back.  Used inside the repeated phases of a looped
+// kernel on the thread index, so that the per-thread addresses derived from it are recomputed in every iteration
+// (a few instructions) rather than computed once, kept across the whole loop and spilled.
+HCNN_HD int opaque(int x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("" : "+v"(x));
+#endif
+  return x;
+}
 
 // ldc(table, i): element i of a read-only table (moduli, twiddles, base-conversion constants).
 // In device code the words are read through the constant address space: with a wave-uniform
@@ -66,6 +80,12 @@ template <class T> inline T ldc(const T* table, size_t i) { return table[i]; }
 template <class T> __device__ __forceinline__ T ldc(const T* table, size_t i) { return table[i]; }
 #endif
 
+// kMinWavesPerSimd (optional): occupancy the register allocation of the kernel must allow
+template <class K, class = void> struct MinWavesPerSimd { static constexpr int value = 1; };
+template <class K> struct MinWavesPerSimd<K, std::void_t<decltype(K::kMinWavesPerSimd)>> { static constexpr int value = K::kMinWavesPerSimd; };
+template <class K, class = void> struct LoopPhases { static constexpr int value = 0; };
+template <class K> struct LoopPhases<K, std::void_t<decltype(K::kLoopPhases)>> { static constexpr int value = K::kLoopPhases; };
+
 #ifdef HCNN_HOSTEMU
 // ------------------------------------------------------------------ host emulation
 inline int dev_malloc(void** p, size_t bytes) {
@@ -84,15 +104,16 @@ inline int event_destroy(hcnn_event_t) { return 0; }
 inline int event_record(hcnn_event_t, hcnn_stream_t) { return 0; }
 inline int event_elapsed_ms(float* ms, hcnn_event_t, hcnn_event_t) { *ms = 0.f; return 0; }
 inline size_t max_lds_bytes() { return 160 * 1024; }
+inline uint32_t compute_unit_count() { return 1; }   // small rounds: the checker's little batches reach every batch-splitting path
 HCNN_HD void atomic_inc64(unsigned long long* p) { *p += 1; }
 HCNN_HD void atomic_max32(uint32_t* p, uint32_t v) { if (v > *p) *p = v; }
 
-template <class K, int PH>
+template <class K, int PH, int END>
 struct EmuPhases {
   template <class Args>
   static void run(const Args& a, unsigned bid, uint32_t* lds, std::vector<typename K::Regs>& regs) {
     for (int tid = 0; tid < K::kThreads; ++tid) K::template phase<PH>(a, bid, tid, lds, regs[tid]);
-    if constexpr (PH + 1 < K::kPhases) EmuPhases<K, PH + 1>::run(a, bid, lds, regs);
+    if constexpr (PH + 1 < END) EmuPhases<K, PH + 1, END>::run(a, bid, lds, regs);
   }
 };
 
@@ -101,7 +122,17 @@ int launch(hcnn_stream_t, size_t grid, size_t lds_bytes, const Args& a) {
   if (lds_bytes > max_lds_bytes()) return 1;
   std::vector<uint32_t> lds(lds_bytes / 4 + 4);
   std::vector<typename K::Regs> regs(K::kThreads);
-  for (size_t bid = 0; bid < grid; ++bid) EmuPhases<K, 0>::run(a, (unsigned)bid, lds.data(), regs);
+  constexpr int LP = LoopPhases<K>::value;
+  for (size_t bid = 0; bid < grid; ++bid) {
+    if constexpr (LP > 0) {
+      const uint32_t count = K::loop_count(a);
+      for (uint32_t it = 0; it < count; ++it) {
+        for (auto& r : regs) r.iter = it;
+        EmuPhases<K, 0, LP>::run(a, (unsigned)bid, lds.data(), regs);
+      }
+    }
+    if constexpr (LP < K::kPhases) EmuPhases<K, LP, K::kPhases>::run(a, (unsigned)bid, lds.data(), regs);
+  }
   return 0;
 }
 
@@ -135,24 +166,39 @@ inline size_t max_lds_bytes() {
   if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return 0;
   return (size_t)v;
 }
+inline uint32_t compute_unit_count() {
+  int dev = 0, v = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
+  return (uint32_t)v;
+}
 HCNN_HD void atomic_inc64(unsigned long long* p) { atomicAdd(p, 1ull); }
 HCNN_HD void atomic_max32(uint32_t* p, uint32_t v) { atomicMax(p, v); }
 
-template <class K, int PH, class Args>
+template <class K, int PH, int END, class Args>
 __device__ __forceinline__ void run_phases(const Args& a, unsigned bid, int tid, uint32_t* lds,
                                            typename K::Regs& regs) {
   K::template phase<PH>(a, bid, tid, lds, regs);
-  if constexpr (PH + 1 < K::kPhases) {
+  if constexpr (PH + 1 < END) {
     __syncthreads();
-    run_phases<K, PH + 1, Args>(a, bid, tid, lds, regs);
+    run_phases<K, PH + 1, END, Args>(a, bid, tid, lds, regs);
   }
 }
 
 template <class K, class Args>
-__global__ void __launch_bounds__(K::kThreads) kernel_entry(const Args a) {
+__global__ void __launch_bounds__(K::kThreads, MinWavesPerSimd<K>::value) kernel_entry(const Args a) {
   extern __shared__ __align__(16) uint32_t hcnn_lds[];
   typename K::Regs regs;
-  run_phases<K, 0, Args>(a, blockIdx.x, (int)threadIdx.x, hcnn_lds, regs);
+  constexpr int LP = LoopPhases<K>::value;
+  if constexpr (LP > 0) {
+    const uint32_t count = K::loop_count(a);
+    for (uint32_t it = 0; it < count; ++it) {
+      regs.iter = it;
+      run_phases<K, 0, LP, Args>(a, blockIdx.x, (int)threadIdx.x, hcnn_lds, regs);
+      __syncthreads();
+    }
+  }
+  if constexpr (LP < K::kPhases) run_phases<K, LP, K::kPhases, Args>(a, blockIdx.x, (int)threadIdx.x, hcnn_lds, regs);
 }
 
 template <class K, class Args>

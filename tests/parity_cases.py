@@ -183,6 +183,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
                        check_decrypt=True, t=65537, expect_k_aux=None, relin_order=None):
     s = Setup(backend, n, k, t=t, seed_id=seed_id)
     if relin_order is not None:
+        s.ctx.set_relin_split(1)             # the order concerns the separate inner-product kernel
         s.ctx.set_relin_order(relin_order)
     if expect_k_aux is not None:
         assert len(s.p) == expect_k_aux
@@ -213,6 +214,13 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
     buf = backend.dev(cts)
     s.ctx.ct_square_relin(buf, out=buf)
     assert np.array_equal(backend.host(buf), want), "square_relin in place"
+    if relin_order is None and n <= 8192:
+        # the same with relinearisation forced into its one-kernel form (small batches take the separate kernels
+        # by default) and into the three separate kernels (the only form for larger rings)
+        for mode in (2, 1):
+            s.ctx.set_relin_split(mode)
+            out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
+            assert np.array_equal(out, want), ("square_relin, relinearisation form", mode, n, k)
     s.ctx.close()
 
 
@@ -451,7 +459,7 @@ def check_samplers(backend, n, k, seed_id=1):
 
 def check_random_sweep(backend, iterations, seed, sizes=(1024, 2048, 4096)):
     """Seeded sweep over random parameter sets and shapes: ring degree, number of primes (1..7), plaintext modulus,
-    ambiguity band, batch size, gather geometry (groups, filters, terms) and weight bounds up to 2^31 - 1, with
+    ambiguity band, form of the relinearisation, batch size, gather geometry (groups, filters, terms) and weight bounds up to 2^31 - 1, with
     extreme residues planted in the inputs; squaring, general product, scalar MAC and noise read-out must equal
     the oracle on every draw."""
     rng = np.random.default_rng(seed)
@@ -465,6 +473,7 @@ def check_random_sweep(backend, iterations, seed, sizes=(1024, 2048, 4096)):
         s.ctx.set_relin_key(backend.dev(s.evk))
         if rng.random() < 0.3:
             s.ctx.set_ambiguity_band(int(2 ** rng.integers(7, 27)))
+        s.ctx.set_relin_split(int(rng.integers(0, 3)))
         n_ct = int(rng.integers(1, 7))
         cts = gen.uniform_residues(s.rng, s.q, n, lead=(n_ct, 2))
         for l, p in enumerate(s.q):

@@ -83,6 +83,30 @@ def test_square_relin_largest_rings_residue_exact(backend):
     pc.check_square_relin(backend, 32768, 6, n_random=1, n_genuine=0)
 
 
+def test_square_relin_whole_rounds_plus_remainder(backend):
+    """A batch that the default policy splits: whole rounds of the one-kernel relinearisation, the rest through the
+    separate kernels.  Sampled ciphertexts against the oracle, every ciphertext against the two forced forms."""
+    say("square_relin n=4096 k=4, 259 ciphertexts: one round in one kernel + three through the separate kernels")
+    n, k = 4096, 4
+    s = pc.Setup(backend, n, k)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    n_ct = 256 + 3                                         # one round of 1024 workgroups at k = 4, and three more
+    cts = gen.uniform_residues(s.rng, s.q, n, lead=(n_ct, 2))
+    dev = backend.dev(cts)
+    s.ctx.set_profile(True)
+    out = backend.host(s.ctx.ct_square_relin(dev))
+    prof = s.ctx.profile()
+    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 256 * k * (k + 2)
+    assert prof["relin_mac"][0] == 1                       # three singles
+    s.ctx.set_profile(False)
+    for i in (0, 131, 255, 256, 258):
+        assert np.array_equal(out[i], fv.square_relin(s.octx, cts[i], s.evk)), i
+    for mode in (1, 2):
+        s.ctx.set_relin_split(mode)
+        assert np.array_equal(backend.host(s.ctx.ct_square_relin(dev)), out), mode
+    s.ctx.close()
+
+
 def test_square_relin_exact_comparison_path(backend):
     say("square_relin forced exact comparison")
     pc.check_square_relin(backend, 1024, 2, force_exact=True)
@@ -244,11 +268,21 @@ def test_options_and_profile(backend):
     ctx.ntt_fwd(x); ctx.ntt_inv(x)
     ctx.ct_square_relin(x)
     prof = ctx.profile()
-    assert prof["ntt_fwd"][0] == 3 and prof["ntt_fwd"][1] == 3 * 2 * 2 + 3 * 2 * 5 + 3 * 4   # rows: plain, ext, digits
+    # three ciphertexts are far from a round of the one-kernel relinearisation: separate kernels
+    assert prof["ntt_fwd"][0] == 3 and prof["ntt_fwd"][1] == 3 * 2 * 2 + 3 * 2 * 5 + 3 * 4   # rows: plain, extended, digits
     assert prof["ntt_inv"][0] == 3 and prof["scale"][0] == 1 and prof["base_ext"][0] == 1
+    assert prof["relin_mac"][0] == 1 and prof["relin_fused"][0] == 0                         # one launch of singles
     assert all(v[2] > 0 for k, v in prof.items() if v[0])
     ctx.reset_stats()
     assert all(v[0] == 0 for v in ctx.profile().values())
+    with pytest.raises(_capi.HcnnError):
+        ctx.set_relin_split(3)
+    ctx.set_relin_split(2)
+    ctx.ct_square_relin(x)
+    prof = ctx.profile()
+    assert prof["ntt_fwd"][0] == 1 and prof["ntt_fwd"][1] == 3 * 2 * 5                       # rows: extended
+    assert prof["ntt_inv"][0] == 1 and prof["relin_mac"][0] == 0
+    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 3 * 2 * (2 + 2)         # k forward + 2 inverse rows each
     assert ctx.scratch_bytes() > 0
     ctx.close()
 
