@@ -817,7 +817,9 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   if (C == 0) {
     const size_t budget = (size_t)6 << 30;   // 6 GiB of scratch (of 288 GB): enough rows per launch at every n
     C = budget / (words_per_ct * 4);
-    if (C > 256) C = 256;
+    const size_t cap = std::max<size_t>(256, fused_round);      // small rings need more ciphertexts to fill the chip
+    if (C > cap) C = cap;
+    if (fused_round && C > fused_round) C = C / fused_round * fused_round;   // whole rounds of the one-kernel relinearisation
   }
   if (C < 1) C = 1;
   if (C > n_ct) C = n_ct;
