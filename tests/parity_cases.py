@@ -240,7 +240,8 @@ def check_mul_relin(backend, n, k, seed_id=1, force_exact=False):
     assert np.array_equal(out[3], fv.square_relin(s.octx, a[3], s.evk))
     m = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[0]), n, s.t)
     assert np.array_equal(m, (slots[0].astype(np.uint64) * slots[1] % s.t).astype(np.uint32))
-    # in place on the first operand
+    # in place on the first operand, relinearisation forced into its one-kernel form
+    s.ctx.set_relin_split(2)
     buf = backend.dev(a)
     s.ctx.ct_mul_relin(buf, backend.dev(b), out=buf)
     assert np.array_equal(backend.host(buf), want)
