@@ -785,10 +785,11 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
 
 // HMult of Sec. 2.1 on n_ct pairs (a_i, b_i); b == nullptr squares a (HSquare).
 // Workgroups of the one-kernel relinearisation that the device holds at a time: its register use allows
-// 8 waves per compute unit at n = 8192 (213 registers, 4 waves per workgroup) and 16 below (128 registers).
+// 8 waves per compute unit at n = 8192 (213 registers, 32 residues per thread, 4 waves per workgroup) and 16 at the
+// other sizes (at most 128 registers, 16 residues per thread).
 static size_t relin_fused_slots(const hcnn_ctx* c) {
-  const size_t waves_per_wg = std::max<size_t>(1, ((size_t)1 << c->logn) / (c->logn >= 13 ? 32 : 16) / 64);
-  const size_t waves_per_cu = c->logn >= 13 ? 8 : 16;
+  const size_t waves_per_wg = std::max<size_t>(1, ((size_t)1 << c->logn) / (c->logn == 13 ? 32 : 16) / 64);
+  const size_t waves_per_cu = c->logn == 13 ? 8 : 16;
   return (size_t)c->compute_units * (waves_per_cu / waves_per_wg);
 }
 
@@ -802,12 +803,14 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   const uint32_t k = c->k, kp = c->kp, L = k + kp, n = c->n;
   const size_t rn = n;
   const size_t ext_rows = in_b ? 4 * (size_t)L : 2 * (size_t)L;
-  // n <= 8192: relinearisation runs as one kernel that needs no buffers for the transformed digits and the sums.
-  // (At n = 16384 a workgroup of that kernel would fill a compute unit alone; measured at half the speed.)
+  // n <= 16384: relinearisation runs as one kernel that needs no buffers for the transformed digits and the sums.
+  // (At n = 16384 its 1024-thread workgroup fills a compute unit alone: measured +5..8 % up to 15 primes, no gain
+  // with the in-loop folds of longer bases, which stay with the separate kernels; at n = 32768 a row and its sums
+  // do not fit the registers of 1024 threads.)
   // Its workgroups are long (k + 2 transforms each), so it only takes whole rounds of resident workgroups; what is
   // left of a batch (all of a small batch) goes through the three separate kernels, which spread k^2 rows per
   // ciphertext over the chip.
-  const bool fused = c->relin_split != 1 && c->logn <= 13;
+  const bool fused = c->relin_split != 1 && (c->logn <= 13 || (c->logn == 14 && k <= 15));
   // (the k workgroups of a ciphertext share a die, for its L2: a round is counted per die)
   const size_t fused_round = fused ? relin_fused_slots(c) / kXcds / k * kXcds : 0;   // ciphertexts per round (0: never)
   const size_t words_main = (ext_rows + 3 * L + 3 * k) * rn;
@@ -884,6 +887,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
         case 11: e = HCNN_FUSED(11, 4); break;
         case 12: e = HCNN_FUSED(12, 4); break;
         case 13: e = HCNN_FUSED(13, 5); break;
+        case 14: e = HCNN_FUSED(14, 4); break;
         default: e = HCNN_ERR_N; break;
       }
 #undef HCNN_FUSED

@@ -460,7 +460,8 @@ struct RelinFused {
   static constexpr int P = G::kPhases;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kLoopPhases = P;
-  static constexpr int kMinWavesPerSimd = G::kThreads / 256 * 2 > 0 ? G::kThreads / 256 * 2 : 1;   // room for two workgroups per compute unit
+  // room for two workgroups per compute unit (one of 1024 threads)
+  static constexpr int kMinWavesPerSimd = G::kThreads >= 1024 ? 4 : (G::kThreads / 256 * 2 > 0 ? G::kThreads / 256 * 2 : 1);
   static constexpr int kPhases = 3 * P;
   using Regs = RelinRegs<G::R>;
   HCNN_HD static uint32_t loop_count(const RelinFusedArgs& a) { return a.k; }

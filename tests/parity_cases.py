@@ -214,7 +214,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
     buf = backend.dev(cts)
     s.ctx.ct_square_relin(buf, out=buf)
     assert np.array_equal(backend.host(buf), want), "square_relin in place"
-    if relin_order is None and n <= 8192:
+    if relin_order is None and n <= 16384:
         # the same with relinearisation forced into its one-kernel form (small batches take the separate kernels
         # by default) and into the three separate kernels (the only form for larger rings)
         for mode in (2, 1):
