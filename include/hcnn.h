@@ -229,7 +229,7 @@ enum {
                                    the key size (default), 1 = ciphertext-major, 2 = key-major (needs
                                    n >= 8192).  Same results either way; for tests and tuning. */
   HCNN_OPT_RELIN_SPLIT = 4      /* relinearisation (HMult step 3) of rings n <= 8192, and of n = 16384 with at
-                                   most 15 primes: 0 (default) = one kernel
+                                   most 16 primes: 0 (default) = one kernel
                                    (digit transforms, inner product with the key and inverse transforms
                                    without leaving the registers) for as many ciphertexts of a batch as fill
                                    whole rounds of its workgroups on the device, the three separate kernels

@@ -804,13 +804,13 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   const size_t rn = n;
   const size_t ext_rows = in_b ? 4 * (size_t)L : 2 * (size_t)L;
   // n <= 16384: relinearisation runs as one kernel that needs no buffers for the transformed digits and the sums.
-  // (At n = 16384 its 1024-thread workgroup fills a compute unit alone: measured +5..8 % up to 15 primes, no gain
+  // (At n = 16384 its 1024-thread workgroup fills a compute unit alone: measured +5..8 % up to 16 primes, no gain
   // with the in-loop folds of longer bases, which stay with the separate kernels; at n = 32768 a row and its sums
   // do not fit the registers of 1024 threads.)
   // Its workgroups are long (k + 2 transforms each), so it only takes whole rounds of resident workgroups; what is
   // left of a batch (all of a small batch) goes through the three separate kernels, which spread k^2 rows per
   // ciphertext over the chip.
-  const bool fused = c->relin_split != 1 && (c->logn <= 13 || (c->logn == 14 && k <= 15));
+  const bool fused = c->relin_split != 1 && (c->logn <= 13 || (c->logn == 14 && k <= 16));
   // (the k workgroups of a ciphertext share a die, for its L2: a round is counted per die)
   const size_t fused_round = fused ? relin_fused_slots(c) / kXcds / k * kXcds : 0;   // ciphertexts per round (0: never)
   const size_t words_main = (ext_rows + 3 * L + 3 * k) * rn;
@@ -880,7 +880,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
       const size_t grid = ntt_grouped_grid(nf * k, k), rows = nf * k * (k + 2);
 #define HCNN_FUSED(LOGN, LOGR)                                                                                      \
   (k <= 8 ? run<RelinFused<LOGN, LOGR, kNttFusedMac>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows)             \
-          : k <= 15 ? run<RelinFused<LOGN, LOGR, kNttFusedMac15>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows) \
+          : k <= 16 ? run<RelinFused<LOGN, LOGR, kNttFusedMac15>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows) \
                     : run<RelinFused<LOGN, LOGR, kNttFusedMacAny>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows))
       switch (c->logn) {
         case 10: e = HCNN_FUSED(10, 4); break;

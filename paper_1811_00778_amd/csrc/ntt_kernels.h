@@ -58,7 +58,7 @@ struct NttLimb {
 //                   the output adds y row (ct, b, j) (`aux`) like kNttStoreAdd and goes to out row (ct, b, j)
 enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4,
              kNttStoreLazy = 5, kNttFusedMac = 6, kNttFromRegs0 = 7, kNttFromRegs1 = 8,
-             kNttFusedMac15 = 9, kNttFusedMacAny = 10 };   // the fused inner product for k <= 8, k <= 15, any k
+             kNttFusedMac15 = 9, kNttFusedMacAny = 10 };   // the fused inner product for k <= 8, k <= 16, any k
 
 // Per-thread state of RelinFused: the iteration (digit) and the two inner-product sums of every residue the
 // thread holds after the last forward pass.
@@ -203,14 +203,14 @@ struct NttFwd {
       if constexpr (kLast && kFused) {
         // The transformed digit times the key rows (below p < 2^30), added to the 64-bit sums.  With the digit only
         // brought into [0, 2p), 8 products stay below 16 p^2 < 2^64 (kNttFusedMac, k <= 8); with the digit made
-        // canonical, 15 products and a residue do (kNttFusedMac15, k <= 15), and kNttFusedMacAny folds the sums
-        // before digits 15, 30, ...
+        // canonical, 16 products do, or 15 and a residue (kNttFusedMac15, k <= 16; the name is historical), and
+        // kNttFusedMacAny folds the sums before digits 16, 31, 46, ...
         const uint32_t* key1 = key0 + (size_t)a.limb_cycle * N;
         uint32_t e0[NET], e1[NET];
 #pragma unroll
         for (int e = 0; e < NET; ++e) { e0[e] = key0[base + (uint32_t)e]; e1[e] = key1[base + (uint32_t)e]; }
         if constexpr (IO == kNttFusedMacAny) {
-          if (regs.iter != 0 && regs.iter % 15 == 0) {
+          if (regs.iter >= 16 && (regs.iter - 16) % 15 == 0) {
 #pragma unroll
             for (int e = 0; e < NET; ++e) {
               regs.s0[c * NET + e] = reduce64(regs.s0[c * NET + e], L.m);
