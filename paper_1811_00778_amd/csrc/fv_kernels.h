@@ -164,7 +164,7 @@ struct ExtKernel {
     uint32_t* gcol = lds + (size_t)ks * kThreads + tid;
     auto in = [&](uint32_t i) { return src[(size_t)i * n]; };
     const uint32_t v = bconv_prepare(a.bc, in, zcol, gcol, kThreads, a.band, a.fallback_counter);
-    for (uint32_t i = 0; i < ks; ++i) dst[(size_t)i * n] = in(i);
+    // (rows 0..ks-1 of `out` are not written: the forward transform reads those limbs from the ciphertext itself)
     for (uint32_t j = 0; j < kd; ++j) dst[(size_t)(ks + j) * n] = bconv_output(a.bc, zcol, kThreads, v, j);
   }
 };
@@ -202,8 +202,7 @@ struct ExtKernelT {
       return garner_gt_half(a.bc, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact, a.fallback_counter);
-#pragma unroll
-    for (int i = 0; i < K; ++i) dst[(size_t)i * n] = x[i];
+    // (rows 0..K-1 of `out` are not written: the forward transform reads those limbs from the ciphertext itself)
     // rolled loop over the destination primes: row j of the transposed table is one contiguous scalar load
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)KP; ++j) {

@@ -522,6 +522,7 @@ struct NttRows {
   uint32_t cycle, limb_base;
   uint32_t in_group_rows, in_row0, out_group_rows, out_row0;
   const uint32_t* aux = nullptr;
+  uint32_t own_limbs = 0;
 };
 
 template <int LOGN, int LOGR>
@@ -534,6 +535,7 @@ int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse, int io) {
   a.in_group_rows = r.in_group_rows; a.in_row0 = r.in_row0;
   a.out_group_rows = r.out_group_rows; a.out_row0 = r.out_row0;
   a.n_rows = (uint32_t)r.rows;
+  a.own_limbs = r.own_limbs;
   const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;
   if (inverse) {
     const size_t g3 = ntt_grouped_grid(r.rows, 3);
@@ -564,8 +566,8 @@ int ntt_rows(hcnn_ctx* c, const NttRows& r, bool inverse, int io = kNttPlain) {
 
 // dense rows [rows][n], limb = base + r % cycle
 int ntt_dense(hcnn_ctx* c, const uint32_t* in, uint32_t* out, size_t rows, uint32_t cycle, bool inverse,
-              int io = kNttPlain, const uint32_t* aux = nullptr) {
-  NttRows r{in, out, rows, cycle, 0, cycle, 0, cycle, 0, aux};
+              int io = kNttPlain, const uint32_t* aux = nullptr, uint32_t own_limbs = 0) {
+  NttRows r{in, out, rows, cycle, 0, cycle, 0, cycle, 0, aux, own_limbs};
   return ntt_rows(c, r, inverse, io);
 }
 
@@ -844,16 +846,17 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
 
   for (size_t c0 = 0; c0 < n_ct; c0 += C) {
     const size_t cc = std::min(C, n_ct - c0);
-    // 1. centred lift of c0, c1 extended to the auxiliary primes; 2. forward NTT over all k + k' limbs
+    // 1. centred lift of c0, c1 extended to the auxiliary primes (only the new rows are written);
+    // 2. forward NTT over all k + k' limbs, the first k read from the ciphertext itself
     ExtArgs ea;
     ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-    if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false, kNttStoreLazy))) return e;
+    if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false, kNttStoreLazy, in + c0 * ct_words, k))) return e;
     if (in_b) {
       ea.in = in_b + c0 * ct_words; ea.out = ext_b;
       if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-      if ((e = ntt_dense(c, ext_b, ext_b, cc * 2 * L, L, false, kNttStoreLazy))) return e;
+      if ((e = ntt_dense(c, ext_b, ext_b, cc * 2 * L, L, false, kNttStoreLazy, in_b + c0 * ct_words, k))) return e;
     }
     // 3+4. tensor formed while loading, then back to coefficients: the integer tensor, known mod q*p
     if (in_b) {

@@ -80,6 +80,8 @@ struct NttArgs {
   uint32_t in_group_rows, in_row0;
   uint32_t out_group_rows, out_row0;
   uint32_t n_rows;          // rows of this launch (the grid may be padded, see ntt_logical_row)
+  uint32_t own_limbs;       // kNttStoreLazy with `aux` set: rows of the first own_limbs limbs of every group are read from
+                            // aux, laid out [group][own_limbs][n] (a ciphertext's own limbs), the others from `in`
 };
 
 // Workgroups are handed to the 8 accelerator dies round-robin by index, and each die has its own
@@ -168,6 +170,10 @@ struct NttFwd {
       gin = a.in + ((size_t)(bid / (kk * kk)) * 3 * kk + 2 * kk + (bid / kk) % kk) * N;
     } else {
       gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
+      if constexpr (IO == kNttStoreLazy) {
+        if (a.aux != nullptr && bid % a.limb_cycle < a.own_limbs)
+          gin = a.aux + ((size_t)(bid / a.limb_cycle) * a.own_limbs + bid % a.limb_cycle) * N;
+      }
     }
     if constexpr (!kFused) gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
 
