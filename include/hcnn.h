@@ -228,13 +228,17 @@ enum {
   HCNN_OPT_RELIN_ORDER = 3,     /* workgroup order of the evaluation-key inner product: 0 = chosen from
                                    the key size (default), 1 = ciphertext-major, 2 = key-major (needs
                                    n >= 8192).  Same results either way; for tests and tuning. */
-  HCNN_OPT_RELIN_SPLIT = 4      /* relinearisation (HMult step 3) of rings n <= 8192, and of n = 16384 with at
-                                   most 16 primes: 0 (default) = one kernel
-                                   (digit transforms, inner product with the key and inverse transforms
-                                   without leaving the registers) for as many ciphertexts of a batch as fill
-                                   whole rounds of its workgroups on the device, the three separate kernels
-                                   for the rest and for small batches; 1 = always the separate kernels;
-                                   2 = always the one kernel.  Same results either way; for tests and tuning. */
+  HCNN_OPT_FUSION = 4           /* one-kernel forms of two parts of HMult that keep their intermediate
+                                   polynomials in registers: the squaring tensor (step 1 with equal operands:
+                                   both forward transforms, the three products and inverse transforms; rings
+                                   n <= 8192) and the relinearisation (step 3: digit transforms, inner product
+                                   with the key, inverse transforms; n <= 8192, and n = 16384 with at most 16
+                                   primes).  0 (default) = chosen per internal batch: the tensor kernel for
+                                   batches of several rounds of its workgroups, the relinearisation kernel for
+                                   as many ciphertexts as fill whole rounds, the separate kernels for the rest
+                                   and for small batches; 1 = always the separate kernels; 2 = always the
+                                   one-kernel forms where the ring allows them.  Same results either way; for
+                                   tests and tuning. */
 };
 int hcnn_set_option(hcnn_ctx* ctx, int which, uint64_t value);
 
@@ -249,7 +253,8 @@ enum {
   HCNN_PROF_NTT_FWD = 0,
   HCNN_PROF_NTT_INV = 1,
   HCNN_PROF_BASE_EXT = 2,    /* centred lift q -> q u p                              */
-  HCNN_PROF_TENSOR = 3,      /* (c0^2, 2 c0 c1, c1^2) slot-wise: fused into NTT_INV, stays 0 */
+  HCNN_PROF_TENSOR = 3,      /* the squaring tensor in one kernel (2 forward + 3 inverse transforms per workgroup;
+                                `blocks` counts transformed rows); 0 where the separate transforms run */
   HCNN_PROF_SCALE = 4,       /* round(t/q .) and return to basis q                   */
   HCNN_PROF_DIGIT = 5,       /* RNS digits of c2 mod every prime: fused into NTT_FWD, stays 0 */
   HCNN_PROF_RELIN_MAC = 6,   /* inner product with the evaluation key                */

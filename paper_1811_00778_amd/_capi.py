@@ -7,7 +7,7 @@ ptr = C.c_void_p
 
 ERR = dict(OK=0, NULL=-1, N=-2, PRIME=-3, T=-4, AUX=-5, ARG=-6, NOKEY=-7, ALIGN=-8, NODEVICE=-9)
 STAT_EXACT_FALLBACKS, STAT_BAD_INPUT, STAT_SCRATCH_BYTES = 0, 1, 2
-OPT_AMBIGUITY_BAND, OPT_SQUARE_CHUNK, OPT_PROFILE, OPT_RELIN_ORDER, OPT_RELIN_SPLIT = 0, 1, 2, 3, 4
+OPT_AMBIGUITY_BAND, OPT_SQUARE_CHUNK, OPT_PROFILE, OPT_RELIN_ORDER, OPT_FUSION = 0, 1, 2, 3, 4
 PROF_CLASSES = ["ntt_fwd", "ntt_inv", "base_ext", "tensor", "scale", "digit", "relin_mac", "relin_add",
                 "scalar_mac", "other", "relin_fused"]
 MAX_LIMBS, MAX_FILTERS = 32, 16

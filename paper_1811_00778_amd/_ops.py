@@ -182,9 +182,9 @@ class OpsMixin:
     def set_relin_order(self, order):
         self.raw.set_option(_capi.OPT_RELIN_ORDER, order)
 
-    def set_relin_split(self, mode):
-        """Form of the relinearisation: 0 chosen per batch, 1 always three separate kernels, 2 always one kernel."""
-        self.raw.set_option(_capi.OPT_RELIN_SPLIT, int(mode))
+    def set_fusion(self, mode):
+        """One-kernel forms of the squaring tensor and the relinearisation: 0 chosen per batch, 1 never, 2 always."""
+        self.raw.set_option(_capi.OPT_FUSION, int(mode))
 
     def set_square_chunk(self, chunk):
         self.raw.set_option(_capi.OPT_SQUARE_CHUNK, chunk)

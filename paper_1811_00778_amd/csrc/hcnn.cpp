@@ -247,7 +247,7 @@ struct hcnn_ctx {
   uint32_t band = 128;
   uint64_t square_chunk = 0;
   uint64_t relin_order = 0;   // 0 = by key size, 1 = ciphertext-major, 2 = key-major
-  uint64_t relin_split = 0;   // 0 = one relinearisation kernel for whole rounds of its workgroups, 1 = never, 2 = always (n <= 8192)
+  uint64_t fusion = 0;   // one-kernel tensor / relinearisation: 0 = chosen per batch, 1 = never, 2 = always where available
   size_t max_lds = 0;
   uint32_t compute_units = 256;
 
@@ -286,6 +286,7 @@ template <int A, int B> struct KernelClass<ScaleKernelR<A, B>> { static constexp
 template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PROF_SCALE; };
 template <int A> struct KernelClass<RelinMacKernel<A>> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
 template <int A, int B, int C> struct KernelClass<RelinFused<A, B, C>> { static constexpr int id = HCNN_PROF_RELIN_FUSED; };
+template <int A, int B> struct KernelClass<TensorFused<A, B>> { static constexpr int id = HCNN_PROF_TENSOR; };
 template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 template <int F> struct KernelClass<MacKernelDirect<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 
@@ -786,7 +787,8 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
 }
 
 // HMult of Sec. 2.1 on n_ct pairs (a_i, b_i); b == nullptr squares a (HSquare).
-// Workgroups of the one-kernel relinearisation that the device holds at a time: its register use allows
+// Workgroups of the one-kernel relinearisation that the device holds at a time (the one-kernel squaring tensor,
+// with 16 waves per compute unit at every size it is used for, holds the same numbers): its register use allows
 // 8 waves per compute unit at n = 8192 (213 registers, 32 residues per thread, 4 waves per workgroup) and 16 at the
 // other sizes (at most 128 registers, 16 residues per thread).
 static size_t relin_fused_slots(const hcnn_ctx* c) {
@@ -812,7 +814,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   // Its workgroups are long (k + 2 transforms each), so it only takes whole rounds of resident workgroups; what is
   // left of a batch (all of a small batch) goes through the three separate kernels, which spread k^2 rows per
   // ciphertext over the chip.
-  const bool fused = c->relin_split != 1 && (c->logn <= 13 || (c->logn == 14 && k <= 16));
+  const bool fused = c->fusion != 1 && (c->logn <= 13 || (c->logn == 14 && k <= 16));
   // (the k workgroups of a ciphertext share a die, for its L2: a round is counted per die)
   const size_t fused_round = fused ? relin_fused_slots(c) / kXcds / k * kXcds : 0;   // ciphertexts per round (0: never)
   const size_t words_main = (ext_rows + 3 * L + 3 * k) * rn;
@@ -855,6 +857,24 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
+    // 2+3 in one kernel for squarings: its workgroups are long (five transforms) and two fit a compute unit at
+    // n = 8192, so it pays from several rounds of workgroups on (measured: +3-5 % from 6 rounds, nothing below)
+    const bool tensor_fused = !in_b && c->logn <= 13 && c->fusion != 1 &&
+                              (c->fusion == 2 || cc * L >= 6 * relin_fused_slots(c));
+    if (tensor_fused) {
+      TensorFusedArgs ta{in + c0 * ct_words, ext, d, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, L, (uint32_t)(cc * L)};
+      const size_t rows = cc * L * 5;
+      switch (c->logn) {
+        case 10: e = run<TensorFused<10, 4>>(c, cc * L, NttGeom<10, 4>::kLdsBytes, ta, rows); break;
+        case 11: e = run<TensorFused<11, 4>>(c, cc * L, NttGeom<11, 4>::kLdsBytes, ta, rows); break;
+        case 12: e = run<TensorFused<12, 4>>(c, cc * L, NttGeom<12, 4>::kLdsBytes, ta, rows); break;
+        // 16 residues per thread also at n = 8192: with the two transformed operands (2 x 16 registers) the kernel
+        // needs 120 registers; at 32 residues per thread it spills
+        case 13: e = run<TensorFused<13, 4>>(c, cc * L, NttGeom<13, 4>::kLdsBytes, ta, rows); break;
+        default: e = HCNN_ERR_N; break;
+      }
+      if (e) return e;
+    } else
     if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false, kNttStoreLazy, in + c0 * ct_words, k))) return e;
     if (in_b) {
       ea.in = in_b + c0 * ct_words; ea.out = ext_b;
@@ -864,7 +884,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     // 3+4. tensor formed while loading, then back to coefficients: the integer tensor, known mod q*p
     if (in_b) {
       if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensorMul, ext_b))) return e;
-    } else {
+    } else if (!tensor_fused) {
       if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensor))) return e;
     }
     // 5. y = round(t/q * d) mod q
@@ -879,7 +899,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
       // a last round joins when it is at least 3/8 full (3/4 if it is the only one): measured break-even points
       const size_t rest = cc - nf;
       if (nf ? rest * 8 >= fused_round * 3 : rest * 4 >= fused_round * 3) nf = cc;
-      if (c->relin_split == 2) nf = cc;
+      if (c->fusion == 2) nf = cc;
     }
     if (nf) {
       RelinFusedArgs fa{y, c->d_evk_hat, out + c0 * ct_words, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, (uint32_t)(nf * k)};
@@ -1209,9 +1229,9 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
       if (value > 2) return HCNN_ERR_ARG;
       c->relin_order = value;
       return HCNN_OK;
-    case HCNN_OPT_RELIN_SPLIT:
+    case HCNN_OPT_FUSION:
       if (value > 2) return HCNN_ERR_ARG;
-      c->relin_split = value;
+      c->fusion = value;
       return HCNN_OK;
   }
   return HCNN_ERR_ARG;

@@ -58,7 +58,17 @@ struct NttLimb {
 //                   the output adds y row (ct, b, j) (`aux`) like kNttStoreAdd and goes to out row (ct, b, j)
 enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4,
              kNttStoreLazy = 5, kNttFusedMac = 6, kNttFromRegs0 = 7, kNttFromRegs1 = 8,
-             kNttFusedMac15 = 9, kNttFusedMacAny = 10 };   // the fused inner product for k <= 8, k <= 16, any k
+             kNttFusedMac15 = 9, kNttFusedMacAny = 10,     // the fused inner product for k <= 8, k <= 16, any k
+             kNttToRegs0 = 11, kNttToRegs1 = 12,           // forward, inside TensorFused: c0 / c1 of workgroup (ct, limb); the
+                                                           // transformed row stays in registers, lazily reduced in [0, 2p)
+             kNttTensorRegs0 = 13, kNttTensorRegs1 = 14, kNttTensorRegs2 = 15 };   // inverse, inside TensorFused: component
+                                                           // b of the tensor formed from those registers (as kNttLoadTensor)
+
+// Per-thread state of TensorFused: the two transformed polynomials of the ciphertext, one limb.
+template <int R>
+struct TensorRegs {
+  uint32_t c0[R], c1[R];
+};
 
 // Per-thread state of RelinFused: the iteration (digit) and the two inner-product sums of every residue the
 // thread holds after the last forward pass.
@@ -130,13 +140,14 @@ struct NttGeom {
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttFwd {
   static constexpr bool kFused = IO == kNttFusedMac || IO == kNttFusedMac15 || IO == kNttFusedMacAny;
-  static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy || kFused,
-                "forward NTT: plain, digit load, lazy store or fused inner product");
+  static constexpr bool kToRegs = IO == kNttToRegs0 || IO == kNttToRegs1;
+  static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy || kFused || kToRegs,
+                "forward NTT: plain, digit load, lazy store, fused inner product or register output");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
   static constexpr bool kDigitIn = IO == kNttLoadDigit || kFused;
-  using Regs = std::conditional_t<kFused, RelinRegs<G::R>, NoRegs>;
+  using Regs = std::conditional_t<kFused, RelinRegs<G::R>, std::conditional_t<kToRegs, TensorRegs<G::R>, NoRegs>>;
 
   template <int PH>
   HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
@@ -144,7 +155,7 @@ struct NttFwd {
     constexpr int S0 = G::s0(PH), NS = G::ns(PH), NET = 1 << NS, C = R / NET;
     constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
     constexpr bool kFirst = PH == 0, kLast = PH == kPhases - 1;
-    if constexpr (kFused) tid = opaque(tid);
+    if constexpr (kFused || kToRegs) tid = opaque(tid);
 
     if constexpr (kDigitIn) {
       bid = ntt_grouped_index(bid, a.limb_cycle);      // the k transforms of one digit row share a die
@@ -168,6 +179,13 @@ struct NttFwd {
     } else if constexpr (IO == kNttLoadDigit) {
       const uint32_t kk = a.limb_cycle;
       gin = a.in + ((size_t)(bid / (kk * kk)) * 3 * kk + 2 * kk + (bid / kk) % kk) * N;
+    } else if constexpr (kToRegs) {
+      // workgroup (ct, l): polynomial c0 or c1 of the ciphertext; its own limbs come from the ciphertext (`aux`,
+      // [ct][2][own_limbs][n]), the auxiliary limbs from the extension buffer (`in`, [ct][2][L][n])
+      const uint32_t LL = a.limb_cycle, poly = IO == kNttToRegs1 ? 1u : 0u;
+      const size_t grp = (size_t)(bid / LL) * 2 + poly;
+      if (bid >= a.n_rows) return;
+      gin = limb < a.own_limbs ? a.aux + (grp * a.own_limbs + limb) * N : a.in + (grp * LL + limb) * N;
     } else {
       gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
       if constexpr (IO == kNttStoreLazy) {
@@ -175,7 +193,7 @@ struct NttFwd {
           gin = a.aux + ((size_t)(bid / a.limb_cycle) * a.own_limbs + bid % a.limb_cycle) * N;
       }
     }
-    if constexpr (!kFused) gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+    if constexpr (!kFused && !kToRegs) gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
 
 #pragma unroll
     for (int c = 0; c < C; ++c) {
@@ -231,6 +249,12 @@ struct NttFwd {
           regs.s0[c * NET + e] += (uint64_t)d * e0[e];
           regs.s1[c * NET + e] += (uint64_t)d * e1[e];
         }
+      } else if constexpr (kLast && kToRegs) {
+#pragma unroll
+        for (int e = 0; e < NET; ++e) {
+          if constexpr (IO == kNttToRegs1) regs.c1[c * NET + e] = csub(v[e], two_p);
+          else                             regs.c0[c * NET + e] = csub(v[e], two_p);
+        }
       } else if constexpr (kLast && NET >= 4) {
         // TLAST == 1: the network is NET consecutive coefficients -> 16-byte stores
         U4* g4 = reinterpret_cast<U4*>(gout + base);
@@ -262,12 +286,14 @@ struct NttFwd {
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttInv {
   static_assert(IO == kNttPlain || IO == kNttLoadTensor || IO == kNttStoreAdd || IO == kNttLoadTensorMul ||
-                IO == kNttFromRegs0 || IO == kNttFromRegs1, "inverse NTT io mode");
+                IO == kNttFromRegs0 || IO == kNttFromRegs1 || IO == kNttTensorRegs0 || IO == kNttTensorRegs1 ||
+                IO == kNttTensorRegs2, "inverse NTT io mode");
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
   static constexpr bool kFromRegs = IO == kNttFromRegs0 || IO == kNttFromRegs1;
-  using Regs = std::conditional_t<kFromRegs, RelinRegs<G::R>, NoRegs>;
+  static constexpr bool kTensorRegs = IO == kNttTensorRegs0 || IO == kNttTensorRegs1 || IO == kNttTensorRegs2;
+  using Regs = std::conditional_t<kFromRegs, RelinRegs<G::R>, std::conditional_t<kTensorRegs, TensorRegs<G::R>, NoRegs>>;
 
   template <int PHI>
   HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
@@ -287,6 +313,10 @@ struct NttInv {
     }
     if constexpr (kFromRegs) {
       bid = ntt_grouped_index(bid, a.limb_cycle);      // the same workgroup -> (ct, j) map as kNttFusedMac
+      if (bid >= a.n_rows) return;
+    }
+    if constexpr (kTensorRegs) {
+      tid = opaque(tid);
       if (bid >= a.n_rows) return;
     }
     const uint32_t limb = a.limb_base + bid % a.limb_cycle;
@@ -314,7 +344,7 @@ struct NttInv {
       // b = 0: c0*c0' ; b = 2: c1*c1' ; b = 1: c0*c1' + c1*c0'
       gin = gmul0 + (comp == 2 ? (size_t)LL * N : 0);
       gin2 = gmul1 + (comp == 0 ? 0 : (size_t)LL * N);
-    } else if constexpr (!kFromRegs) {
+    } else if constexpr (!kFromRegs && !kTensorRegs) {
       gin = a.in + ntt_row(bid, a.limb_cycle, a.in_group_rows, a.in_row0) * N;
     }
     uint32_t* gout;
@@ -323,6 +353,9 @@ struct NttInv {
       const uint32_t kk = a.limb_cycle, ct = bid / kk, b = IO == kNttFromRegs1 ? 1u : 0u;
       gout = a.out + ((size_t)(ct * 2 + b) * kk + bid % kk) * N;
       gaux = a.aux + ((size_t)(ct * 3 + b) * kk + bid % kk) * N;
+    } else if constexpr (kTensorRegs) {
+      const uint32_t LL = a.limb_cycle, b = IO == kNttTensorRegs0 ? 0u : (IO == kNttTensorRegs1 ? 1u : 2u);
+      gout = a.out + ((size_t)((bid / LL) * 3 + b) * LL + bid % LL) * N;       // d row (ct, b, l)
     } else {
       gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
     }
@@ -343,6 +376,17 @@ struct NttInv {
 #pragma unroll
         for (int e = 0; e < NET; ++e)
           v[e] = reduce64(IO == kNttFromRegs1 ? regs.s1[c * NET + e] : regs.s0[c * NET + e], L.m);
+      } else if constexpr (kFirst && kTensorRegs) {
+        // c0^*c0^, 2*c0^*c1^ or c1^*c1^ from the registers of the two forward transforms (values in [0, 2p)); products
+        // carry the factor 2^-32 of the reduction and stay in [0, 2p)
+#pragma unroll
+        for (int e = 0; e < NET; ++e) {
+          const uint32_t x = IO == kNttTensorRegs2 ? regs.c1[c * NET + e] : regs.c0[c * NET + e];
+          const uint32_t y = IO == kNttTensorRegs0 ? regs.c0[c * NET + e] : regs.c1[c * NET + e];
+          uint32_t t = redc_2p((uint64_t)x * y, p, L.pinv);
+          if constexpr (IO == kNttTensorRegs1) t = csub(2 * t, two_p);
+          v[e] = t;
+        }
       } else if constexpr (kFirst && NET >= 4) {
         // TLAST == 1: NET consecutive coefficients -> 16-byte loads
         const U4* g4 = reinterpret_cast<const U4*>(gin + base);
@@ -404,7 +448,7 @@ struct NttInv {
         const bool top = kLast && l == 0;                 // node 1: fold in n^-1
 #pragma unroll
         for (int h = 0; h < (1 << l); ++h) {
-          constexpr bool kMont = IO == kNttLoadTensor || IO == kNttLoadTensorMul;
+          constexpr bool kMont = IO == kNttLoadTensor || IO == kNttLoadTensorMul || kTensorRegs;
           const ShoupConst w = top ? (kMont ? L.w1ninv_r : L.w1ninv) : ldc(tw, (root << l) + h);
           const ShoupConst nv = kMont ? L.ninv_r : L.ninv;
 #pragma unroll
@@ -431,7 +475,7 @@ struct NttInv {
 #pragma unroll
         for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = add_mod(csub(v[e], p), addend[e], p);
       } else if constexpr (kLast) {
-        constexpr bool kLazyOut = IO == kNttLoadTensor || IO == kNttLoadTensorMul;
+        constexpr bool kLazyOut = IO == kNttLoadTensor || IO == kNttLoadTensorMul || kTensorRegs;
 #pragma unroll
         for (int e = 0; e < NET; ++e) gout[base + (uint32_t)e * TLAST] = kLazyOut ? v[e] : csub(v[e], p);
       } else {
@@ -483,6 +527,47 @@ struct RelinFused {
       na.aux = a.y; na.out = a.out; na.tw = a.tw_inv;
       if constexpr (PH < 2 * P) Inv0::template phase<PH - P>(na, bid, tid, lds, regs);
       else Inv1::template phase<PH - 2 * P>(na, bid, tid, lds, regs);
+    }
+  }
+};
+
+// ------------------------------------------------------------------------- squaring tensor in one kernel
+// Workgroup (ct, l): forward transforms of c0 and c1 modulo limb l (l < k: read from the ciphertext; else from the
+// extension buffer), kept in registers, then the three tensor components c0^2, 2 c0 c1, c1^2 through the inverse
+// transform into d[ct][b][l] (HMult step 1 with both operands equal).  The transformed operands never touch memory.
+struct TensorFusedArgs {
+  const uint32_t* cts;      // [n_ct][2][k][n]
+  const uint32_t* ext;      // [n_ct][2][L][n], rows k..L-1 of every polynomial valid
+  uint32_t* d;              // [n_ct][3][L][n]
+  const ShoupConst* tw_fwd;
+  const ShoupConst* tw_inv;
+  const NttLimb* limbs;
+  uint32_t k, L;
+  uint32_t n_rows;          // n_ct * L
+};
+
+template <int LOGN, int LOGR>
+struct TensorFused {
+  using G = NttGeom<LOGN, LOGR>;
+  static constexpr int P = G::kPhases;
+  static constexpr int kThreads = G::kThreads;
+  static constexpr int kPhases = 5 * P;
+  static constexpr int kMinWavesPerSimd = 4;     // 128 registers: two 512-thread or four 256-thread workgroups per compute unit
+  using Regs = TensorRegs<G::R>;
+
+  template <int PH>
+  HCNN_HD static void phase(const TensorFusedArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
+    NttArgs na{};
+    na.limbs = a.limbs; na.limb_cycle = a.L; na.limb_base = 0; na.n_rows = a.n_rows;
+    if constexpr (PH < 2 * P) {
+      na.in = a.ext; na.aux = a.cts; na.own_limbs = a.k; na.tw = a.tw_fwd;
+      if constexpr (PH < P) NttFwd<LOGN, LOGR, kNttToRegs0>::template phase<PH>(na, bid, tid, lds, regs);
+      else NttFwd<LOGN, LOGR, kNttToRegs1>::template phase<PH - P>(na, bid, tid, lds, regs);
+    } else {
+      na.out = a.d; na.tw = a.tw_inv;
+      if constexpr (PH < 3 * P) NttInv<LOGN, LOGR, kNttTensorRegs0>::template phase<PH - 2 * P>(na, bid, tid, lds, regs);
+      else if constexpr (PH < 4 * P) NttInv<LOGN, LOGR, kNttTensorRegs1>::template phase<PH - 3 * P>(na, bid, tid, lds, regs);
+      else NttInv<LOGN, LOGR, kNttTensorRegs2>::template phase<PH - 4 * P>(na, bid, tid, lds, regs);
     }
   }
 };

@@ -183,7 +183,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
                        check_decrypt=True, t=65537, expect_k_aux=None, relin_order=None):
     s = Setup(backend, n, k, t=t, seed_id=seed_id)
     if relin_order is not None:
-        s.ctx.set_relin_split(1)             # the order concerns the separate inner-product kernel
+        s.ctx.set_fusion(1)             # the order concerns the separate inner-product kernel
         s.ctx.set_relin_order(relin_order)
     if expect_k_aux is not None:
         assert len(s.p) == expect_k_aux
@@ -218,7 +218,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
         # the same with relinearisation forced into its one-kernel form (small batches take the separate kernels
         # by default) and into the three separate kernels (the only form for larger rings)
         for mode in (2, 1):
-            s.ctx.set_relin_split(mode)
+            s.ctx.set_fusion(mode)
             out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
             assert np.array_equal(out, want), ("square_relin, relinearisation form", mode, n, k)
     s.ctx.close()
@@ -241,7 +241,7 @@ def check_mul_relin(backend, n, k, seed_id=1, force_exact=False):
     m = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[0]), n, s.t)
     assert np.array_equal(m, (slots[0].astype(np.uint64) * slots[1] % s.t).astype(np.uint32))
     # in place on the first operand, relinearisation forced into its one-kernel form
-    s.ctx.set_relin_split(2)
+    s.ctx.set_fusion(2)
     buf = backend.dev(a)
     s.ctx.ct_mul_relin(buf, backend.dev(b), out=buf)
     assert np.array_equal(backend.host(buf), want)
@@ -474,7 +474,7 @@ def check_random_sweep(backend, iterations, seed, sizes=(1024, 2048, 4096)):
         s.ctx.set_relin_key(backend.dev(s.evk))
         if rng.random() < 0.3:
             s.ctx.set_ambiguity_band(int(2 ** rng.integers(7, 27)))
-        s.ctx.set_relin_split(int(rng.integers(0, 3)))
+        s.ctx.set_fusion(int(rng.integers(0, 3)))
         n_ct = int(rng.integers(1, 7))
         cts = gen.uniform_residues(s.rng, s.q, n, lead=(n_ct, 2))
         for l, p in enumerate(s.q):

@@ -102,7 +102,7 @@ def test_square_relin_whole_rounds_plus_remainder(backend):
     for i in (0, 131, 255, 256, 258):
         assert np.array_equal(out[i], fv.square_relin(s.octx, cts[i], s.evk)), i
     for mode in (1, 2):
-        s.ctx.set_relin_split(mode)
+        s.ctx.set_fusion(mode)
         assert np.array_equal(backend.host(s.ctx.ct_square_relin(dev)), out), mode
     s.ctx.close()
 
@@ -271,17 +271,17 @@ def test_options_and_profile(backend):
     # three ciphertexts are far from a round of the one-kernel relinearisation: separate kernels
     assert prof["ntt_fwd"][0] == 3 and prof["ntt_fwd"][1] == 3 * 2 * 2 + 3 * 2 * 5 + 3 * 4   # rows: plain, extended, digits
     assert prof["ntt_inv"][0] == 3 and prof["scale"][0] == 1 and prof["base_ext"][0] == 1
-    assert prof["relin_mac"][0] == 1 and prof["relin_fused"][0] == 0                         # one launch of singles
+    assert prof["relin_mac"][0] == 1 and prof["relin_fused"][0] == 0 and prof["tensor"][0] == 0   # one launch of singles
     assert all(v[2] > 0 for k, v in prof.items() if v[0])
     ctx.reset_stats()
     assert all(v[0] == 0 for v in ctx.profile().values())
     with pytest.raises(_capi.HcnnError):
-        ctx.set_relin_split(3)
-    ctx.set_relin_split(2)
+        ctx.set_fusion(3)
+    ctx.set_fusion(2)
     ctx.ct_square_relin(x)
     prof = ctx.profile()
-    assert prof["ntt_fwd"][0] == 1 and prof["ntt_fwd"][1] == 3 * 2 * 5                       # rows: extended
-    assert prof["ntt_inv"][0] == 1 and prof["relin_mac"][0] == 0
+    assert prof["ntt_fwd"][0] == 0 and prof["ntt_inv"][0] == 0 and prof["relin_mac"][0] == 0
+    assert prof["tensor"][0] == 1 and prof["tensor"][1] == 3 * 5 * 5                         # 2 forward + 3 inverse rows per (ct, limb)
     assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 3 * 2 * (2 + 2)         # k forward + 2 inverse rows each
     assert ctx.scratch_bytes() > 0
     ctx.close()
