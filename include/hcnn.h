@@ -231,7 +231,7 @@ enum {
   HCNN_OPT_FUSION = 4           /* one-kernel forms of two parts of HMult that keep their intermediate
                                    polynomials in registers: the squaring tensor (step 1 with equal operands:
                                    both forward transforms, the three products and inverse transforms; rings
-                                   n <= 8192) and the relinearisation (step 3: digit transforms, inner product
+                                   n <= 16384) and the relinearisation (step 3: digit transforms, inner product
                                    with the key, inverse transforms; n <= 8192, and n = 16384 with at most 16
                                    primes).  0 (default) = chosen per internal batch: the tensor kernel for
                                    batches of several rounds of its workgroups, the relinearisation kernel for

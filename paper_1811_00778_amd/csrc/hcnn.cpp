@@ -858,8 +858,9 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
     // 2+3 in one kernel for squarings: its workgroups are long (five transforms) and two fit a compute unit at
-    // n = 8192, so it pays from several rounds of workgroups on (measured: +3-5 % from 6 rounds, nothing below)
-    const bool tensor_fused = !in_b && c->logn <= 13 && c->fusion != 1 &&
+    // n = 8192 (one at n = 16384), so it pays from several rounds of workgroups on (measured: +3-5 % from 6 rounds,
+    // nothing below)
+    const bool tensor_fused = !in_b && c->logn <= 14 && c->fusion != 1 &&
                               (c->fusion == 2 || cc * L >= 6 * relin_fused_slots(c));
     if (tensor_fused) {
       TensorFusedArgs ta{in + c0 * ct_words, ext, d, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, L, (uint32_t)(cc * L)};
@@ -871,6 +872,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
         // 16 residues per thread also at n = 8192: with the two transformed operands (2 x 16 registers) the kernel
         // needs 120 registers; at 32 residues per thread it spills
         case 13: e = run<TensorFused<13, 4>>(c, cc * L, NttGeom<13, 4>::kLdsBytes, ta, rows); break;
+        case 14: e = run<TensorFused<14, 4>>(c, cc * L, NttGeom<14, 4>::kLdsBytes, ta, rows); break;
         default: e = HCNN_ERR_N; break;
       }
       if (e) return e;
