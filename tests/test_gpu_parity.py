@@ -107,6 +107,14 @@ def test_square_relin_whole_rounds_plus_remainder(backend):
     s.ctx.close()
 
 
+@pytest.mark.parametrize("n,k", [(8192, 3), (8192, 5), (8192, 7), (8192, 9), (8192, 12), (4096, 6), (16384, 3), (16384, 5)])
+def test_square_relin_every_form_at_the_large_rings(backend, n, k):
+    """Whole ciphertexts against the oracle at the ring sizes of the paper's parameter sets with prime counts off
+    the specialised base-conversion sizes; default policy, one-kernel forms and separate kernels each."""
+    say("square_relin, all forms, n=%d k=%d" % (n, k))
+    pc.check_square_relin(backend, n, k, n_random=1, n_genuine=1, seed_id=k, check_decrypt=not (n == 16384 and k < 5))
+
+
 def test_square_relin_exact_comparison_path(backend):
     say("square_relin forced exact comparison")
     pc.check_square_relin(backend, 1024, 2, force_exact=True)
