@@ -332,6 +332,12 @@ def main():
                             hbm_GBps=round(bytes_per_launch / avg_s / 1e9, 1),
                             hbm_frac=round(bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, 4),
                             avg_launch_ms=round(avg_s * 1e3, 5))
+            # what the counters say of the same kernels (profiles/ntt_issue_counters.md): compiled VALU instructions
+            # per algorithmic butterfly instruction, and the share of all VALU issue slots the kernel fills at the
+            # clock the chip holds under this load (2.1-2.2 GHz, not the nominal 2.4 GHz of `peak`)
+            counters = {"ntt_fwd": (1.12, 0.84), "ntt_inv": (1.18, 0.81), "relin_fused": (1.26, 0.77)}[dom]
+            roofline["counters"] = dict(compiled_over_algorithmic_instr=counters[0], valu_issue_slot_use=counters[1],
+                                        source="profiles/ntt_issue_counters.md")
         else:
             roofline = dict(kernel=dom, bound="alu", achieved=None, peak=ALU_PEAK_TOPS, unit="T int32 lane-instr/s",
                             frac=None, traffic=None, avg_launch_ms=round(avg_s * 1e3, 5))
