@@ -908,7 +908,7 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
       const size_t grid = ntt_grouped_grid(nf * k, k), rows = nf * k * (k + 2);
 #define HCNN_FUSED(LOGN, LOGR)                                                                                      \
   (k <= 8 ? run<RelinFused<LOGN, LOGR, kNttFusedMac>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows)             \
-          : k <= 16 ? run<RelinFused<LOGN, LOGR, kNttFusedMac15>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows) \
+          : k <= 16 ? run<RelinFused<LOGN, LOGR, kNttFusedMac16>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows) \
                     : run<RelinFused<LOGN, LOGR, kNttFusedMacAny>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows))
       switch (c->logn) {
         case 10: e = HCNN_FUSED(10, 4); break;

@@ -58,7 +58,7 @@ struct NttLimb {
 //                   the output adds y row (ct, b, j) (`aux`) like kNttStoreAdd and goes to out row (ct, b, j)
 enum NttIo { kNttPlain = 0, kNttLoadDigit = 1, kNttLoadTensor = 2, kNttStoreAdd = 3, kNttLoadTensorMul = 4,
              kNttStoreLazy = 5, kNttFusedMac = 6, kNttFromRegs0 = 7, kNttFromRegs1 = 8,
-             kNttFusedMac15 = 9, kNttFusedMacAny = 10,     // the fused inner product for k <= 8, k <= 16, any k
+             kNttFusedMac16 = 9, kNttFusedMacAny = 10,     // the fused inner product for k <= 8, k <= 16, any k
              kNttToRegs0 = 11, kNttToRegs1 = 12,           // forward, inside TensorFused: c0 / c1 of workgroup (ct, limb); the
                                                            // transformed row stays in registers, lazily reduced in [0, 2p)
              kNttTensorRegs0 = 13, kNttTensorRegs1 = 14, kNttTensorRegs2 = 15 };   // inverse, inside TensorFused: component
@@ -139,7 +139,7 @@ struct NttGeom {
 // ------------------------------------------------------------------------- forward
 template <int LOGN, int LOGR, int IO = kNttPlain>
 struct NttFwd {
-  static constexpr bool kFused = IO == kNttFusedMac || IO == kNttFusedMac15 || IO == kNttFusedMacAny;
+  static constexpr bool kFused = IO == kNttFusedMac || IO == kNttFusedMac16 || IO == kNttFusedMacAny;
   static constexpr bool kToRegs = IO == kNttToRegs0 || IO == kNttToRegs1;
   static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy || kFused || kToRegs,
                 "forward NTT: plain, digit load, lazy store, fused inner product or register output");
@@ -227,7 +227,7 @@ struct NttFwd {
       if constexpr (kLast && kFused) {
         // The transformed digit times the key rows (below p < 2^30), added to the 64-bit sums.  With the digit only
         // brought into [0, 2p), 8 products stay below 16 p^2 < 2^64 (kNttFusedMac, k <= 8); with the digit made
-        // canonical, 16 products do, or 15 and a residue (kNttFusedMac15, k <= 16; the name is historical), and
+        // canonical, 16 products do, or 15 and a residue (kNttFusedMac16, k <= 16), and
         // kNttFusedMacAny folds the sums before digits 16, 31, 46, ...
         const uint32_t* key1 = key0 + (size_t)a.limb_cycle * N;
         uint32_t e0[NET], e1[NET];
