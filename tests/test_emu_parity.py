@@ -56,6 +56,26 @@ def test_square_relin_chunked_ragged(backend):
     pc.check_square_relin(backend, 1024, 3, n_random=2, n_genuine=0, chunk=2, relin_order=1)   # ciphertext-major order forced
 
 
+def test_square_relin_batch_split_into_rounds_and_remainder(backend):
+    """This build counts one compute unit (16 waves: at n = 1024, two primes, a round of the one-kernel relinearisation is
+    8 ciphertexts and six rounds of the one-kernel tensor are 96 (ciphertext, limb) pairs), so a batch of 26 takes the
+    default policy's mixed route: the tensor in one kernel, 24 ciphertexts through the one-kernel relinearisation, 2
+    through the separate kernels."""
+    s = pc.Setup(backend, 1024, 2)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    n_ct, L = 26, 2 + len(s.p)
+    cts = pc.gen.uniform_residues(s.rng, s.q, 1024, lead=(n_ct, 2))
+    s.ctx.set_profile(True)
+    out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
+    prof = s.ctx.profile()
+    assert prof["tensor"][0] == 1 and prof["tensor"][1] == n_ct * L * 5
+    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 24 * 2 * (2 + 2)
+    assert prof["relin_mac"][0] == 1 and prof["ntt_fwd"][1] == 2 * 2 * 2            # the two left over: digit rows only
+    for i in (0, 23, 24, 25):
+        assert np.array_equal(out[i], pc.fv.square_relin(s.octx, cts[i], s.evk)), i
+    s.ctx.close()
+
+
 def test_square_relin_exact_comparison_path(backend):
     pc.check_square_relin(backend, 1024, 2, force_exact=True)
     pc.check_square_relin(backend, 2048, 4, n_random=1, n_genuine=1, force_exact=True)
