@@ -57,12 +57,15 @@ enum {
   HCNN_ERR_ARG = -6,      /* a count or size is zero, too large, or inconsistent            */
   HCNN_ERR_NOKEY = -7,    /* hcnn_ct_square_relin before hcnn_set_relin_key                 */
   HCNN_ERR_ALIGN = -8,    /* a device pointer is not 16-byte aligned                        */
-  HCNN_ERR_NODEVICE = -9  /* no usable gfx950 device / LDS too small for this n             */
+  HCNN_ERR_NODEVICE = -9, /* no usable gfx950 device / LDS too small for this n             */
+  HCNN_ERR_SCRATCH = -10  /* hcnn_ct_square_relin_noalloc: the parameter set needs more than
+                             HCNN_STATIC_SCRATCH_BYTES for one ciphertext                   */
 };
 
 /* Limits. */
 #define HCNN_MAX_LIMBS 32u        /* k <= 32 and k' <= 32 */
 #define HCNN_MAX_FILTERS 16u      /* F of hcnn_ct_scalar_mac */
+#define HCNN_STATIC_SCRATCH_BYTES (128u << 20)   /* work array of hcnn_ct_square_relin_noalloc, per device */
 
 /* ---- parameter helpers (host only, no device needed) ------------------------------- */
 
@@ -139,6 +142,22 @@ int hcnn_ct_scalar_mac(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_in,
  * Needs k_aux auxiliary primes and hcnn_set_relin_key. */
 int hcnn_ct_square_relin(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_ct,
                          uint32_t* out_cts_dev);
+
+/* hcnn_ct_square_relin for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result, same kernels; the intermediate
+ * polynomials live in a static device array of HCNN_STATIC_SCRATCH_BYTES (128 MiB) inside the library instead of a
+ * buffer from hipMalloc, and the call makes no hipMalloc / hipFree (no first-call warm-up is needed for that).
+ * The batch is processed in internal batches of as many ciphertexts as fit the array:
+ *   5(k+k') + 3k + k^2 + 2k polynomial rows of 4n bytes per ciphertext (5.9 MiB at n = 8192, k = 8;
+ *   118 MiB at n = 32768, k = 24); any n_ct is accepted.
+ * A parameter set whose single ciphertext exceeds the array (e.g. n = 32768 with 30 primes) is refused with
+ * HCNN_ERR_SCRATCH before anything is enqueued.  Launches of this call are not recorded by HCNN_OPT_PROFILE.
+ * Every device that loads the library holds one such array until the process ends, and all contexts on a device
+ * share it: calls of this entry point that overlap in time on one device (two streams, two threads) race on it and
+ * must be serialised by the caller.  Calls on one stream are ordered and safe; nothing has to be cleared between
+ * calls (every word that is read was written earlier in the same call). */
+int hcnn_ct_square_relin_noalloc(hcnn_ctx* ctx, const uint32_t* in_cts_dev, size_t n_ct,
+                                 uint32_t* out_cts_dev);
 
 /* General HMult of Sec. 2.1 (Table "FHE primitives benchmarks", not used by the paper's networks):
  * out_i = Relinearize(round(t/q * a_i (x) b_i)) with the tensor (c0 c0', c0 c1' + c1 c0', c1 c1') over

@@ -5,7 +5,7 @@ u32p = C.POINTER(C.c_uint32)
 u64p = C.POINTER(C.c_uint64)
 ptr = C.c_void_p
 
-ERR = dict(OK=0, NULL=-1, N=-2, PRIME=-3, T=-4, AUX=-5, ARG=-6, NOKEY=-7, ALIGN=-8, NODEVICE=-9)
+ERR = dict(OK=0, NULL=-1, N=-2, PRIME=-3, T=-4, AUX=-5, ARG=-6, NOKEY=-7, ALIGN=-8, NODEVICE=-9, SCRATCH=-10)
 STAT_EXACT_FALLBACKS, STAT_BAD_INPUT, STAT_SCRATCH_BYTES = 0, 1, 2
 OPT_AMBIGUITY_BAND, OPT_SQUARE_CHUNK, OPT_PROFILE, OPT_RELIN_ORDER, OPT_FUSION = 0, 1, 2, 3, 4
 PROF_CLASSES = ["ntt_fwd", "ntt_inv", "base_ext", "tensor", "scale", "digit", "relin_mac", "relin_add",
@@ -24,6 +24,7 @@ SIGNATURES = {
     "hcnn_ntt_inv": [ptr, ptr, C.c_size_t],
     "hcnn_ct_scalar_mac": [ptr, ptr, C.c_size_t, ptr, ptr, C.c_int32, C.c_size_t, C.c_size_t, C.c_size_t, ptr],
     "hcnn_ct_square_relin": [ptr, ptr, C.c_size_t, ptr],
+    "hcnn_ct_square_relin_noalloc": [ptr, ptr, C.c_size_t, ptr],
     "hcnn_ct_mul_relin": [ptr, ptr, ptr, C.c_size_t, ptr],
     "hcnn_keygen": [ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr],
     "hcnn_encrypt": [ptr, ptr, ptr, ptr, ptr, ptr, C.c_size_t, ptr],

@@ -77,6 +77,16 @@ class OpsMixin:
         self.raw.call("hcnn_ct_square_relin", self._ptr(in_cts), n_ct, self._ptr(out))
         return out
 
+    def ct_square_relin_noalloc(self, in_cts, out):
+        """ct_square_relin for callers that cannot allocate: `out` is required, the library works in its static
+        device array and calls no allocator (hcnn_ct_square_relin_noalloc)."""
+        self._check(in_cts, "u32"); self._check(out, "u32")
+        n_ct = self._count(in_cts, self.ct_shape)
+        if tuple(out.shape) != tuple(in_cts.shape):
+            raise ValueError("out must have the shape of in_cts")
+        self.raw.call("hcnn_ct_square_relin_noalloc", self._ptr(in_cts), n_ct, self._ptr(out))
+        return out
+
     def ct_mul_relin(self, a_cts, b_cts, out=None):
         """HMult of every pair (a_i, b_i), with scaling and relinearisation (hcnn_ct_mul_relin)."""
         self._check(a_cts, "u32"); self._check(b_cts, "u32")

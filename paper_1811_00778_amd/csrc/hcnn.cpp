@@ -4,6 +4,7 @@
 #include "../../include/hcnn.h"
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -210,6 +211,49 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace
 
+// ---------------------------------------------------------------- scratch of the entry point that allocates nothing
+// hcnn_ct_square_relin_noalloc keeps the intermediate polynomials of its internal batch in this array instead of a
+// buffer from hipMalloc.  Every device that loads the library holds its own copy (at its own address) until the
+// process ends; every call on a device shares that copy.
+constexpr size_t kStaticScratchBytes = (size_t)128 << 20;
+#ifdef HCNN_HOSTEMU
+alignas(256) static uint32_t scratch[kStaticScratchBytes / 4];
+#else
+static __device__ __align__(256) uint32_t scratch[kStaticScratchBytes / 4];
+#endif
+
+namespace {
+#ifndef HCNN_HOSTEMU
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t* g_scratch_addr[kMaxDevices] = {};
+#endif
+
+// Device address of `scratch` on the current device, looked up once per device.  (In host code the array's name is
+// only a handle for the lookup: kernels and copies take the address returned here.)
+int static_scratch_of_current_device(uint32_t** out) {
+#ifdef HCNN_HOSTEMU
+  *out = scratch;
+  return 0;
+#else
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return HCNN_ERR_NODEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!ptr) return HCNN_ERR_NODEVICE;
+    g_scratch_addr[dev] = (uint32_t*)ptr;
+  }
+  *out = g_scratch_addr[dev];
+  return 0;
+#endif
+}
+}  // namespace
+
 // ---------------------------------------------------------------- context
 struct BConvHost {
   uint32_t ks = 0, kd = 0;
@@ -241,8 +285,9 @@ struct hcnn_ctx {
   uint32_t* d_evk_hat = nullptr;
   bool has_key = false;
 
-  uint32_t* scratch = nullptr;
-  size_t scratch_bytes = 0;
+  uint32_t* work = nullptr;       // device work buffer of the entry points that may allocate (grown on demand)
+  size_t work_bytes = 0;
+  uint32_t* static_scratch = nullptr;   // this device's copy of the file-scope array `scratch` (kStaticScratchBytes)
 
   uint32_t band = 128;
   uint64_t square_chunk = 0;
@@ -498,20 +543,20 @@ int build_tables(hcnn_ctx* c) {
   return 0;
 }
 
-int ensure_scratch(hcnn_ctx* c, size_t bytes) {
-  if (bytes <= c->scratch_bytes) return 0;
-  if (c->scratch) {
+int ensure_work(hcnn_ctx* c, size_t bytes) {
+  if (bytes <= c->work_bytes) return 0;
+  if (c->work) {
     int e = stream_sync(c->stream);
     if (e) return e;
-    dev_free(c->scratch);
-    c->scratch = nullptr;
-    c->scratch_bytes = 0;
+    dev_free(c->work);
+    c->work = nullptr;
+    c->work_bytes = 0;
   }
   void* ptr = nullptr;
   int e = dev_malloc(&ptr, bytes);
   if (e) return e;
-  c->scratch = (uint32_t*)ptr;
-  c->scratch_bytes = bytes;
+  c->work = (uint32_t*)ptr;
+  c->work_bytes = bytes;
   return 0;
 }
 
@@ -697,6 +742,7 @@ int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, u
     return HCNN_ERR_NODEVICE;
   }
   e = build_tables(c);
+  if (!e) e = static_scratch_of_current_device(&c->static_scratch);
   if (e) {
     hcnn_ctx_destroy(c);
     return e;
@@ -712,7 +758,7 @@ int hcnn_ctx_destroy(hcnn_ctx* c) {
   for (auto ev : c->free_events) event_destroy(ev);
   for (void* p : c->owned) dev_free(p);
   if (c->d_evk_hat) dev_free(c->d_evk_hat);
-  if (c->scratch) dev_free(c->scratch);
+  if (c->work) dev_free(c->work);
   delete c;
   return HCNN_OK;
 }
@@ -797,16 +843,21 @@ static size_t relin_fused_slots(const hcnn_ctx* c) {
   return (size_t)c->compute_units * (waves_per_cu / waves_per_wg);
 }
 
-static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b, size_t n_ct, uint32_t* out) {
+// static_ws: the intermediate polynomials go to this device's copy of the file-scope array `scratch` and nothing is
+// allocated; a parameter set whose single ciphertext does not fit that array is refused.
+static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b, size_t n_ct, uint32_t* out,
+                          bool static_ws = false) {
   if (!c) return HCNN_ERR_NULL;
   if (n_ct == 0) return HCNN_OK;
   if (!in || !out) return HCNN_ERR_NULL;
   if (!aligned16(in) || !aligned16(out) || !aligned16(in_b)) return HCNN_ERR_ALIGN;
   if (c->kp == 0) return HCNN_ERR_AUX;
-  if (!c->has_key) return HCNN_ERR_NOKEY;
   const uint32_t k = c->k, kp = c->kp, L = k + kp, n = c->n;
   const size_t rn = n;
   const size_t ext_rows = in_b ? 4 * (size_t)L : 2 * (size_t)L;
+  if (static_ws && (ext_rows + 3 * L + 3 * k + (size_t)k * k + 2 * k) * rn * 4 > kStaticScratchBytes)
+    return HCNN_ERR_SCRATCH;
+  if (!c->has_key) return HCNN_ERR_NOKEY;
   // n <= 16384: relinearisation runs as one kernel that needs no buffers for the transformed digits and the sums.
   // (At n = 16384 its 1024-thread workgroup fills a compute unit alone: measured +5..8 % up to 16 primes, no gain
   // with the in-loop folds of longer bases, which stay with the separate kernels; at n = 32768 a row and its sums
@@ -821,8 +872,10 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   const size_t words_split = ((size_t)k * k + 2 * k) * rn;
   const size_t words_per_ct = words_main + words_split;
   size_t C = c->square_chunk;
+  // 6 GiB of work buffer (of 288 GB): enough rows per launch at every n
+  const size_t budget = static_ws ? kStaticScratchBytes : (size_t)6 << 30;
+  if (static_ws && C > budget / (words_per_ct * 4)) C = 0;
   if (C == 0) {
-    const size_t budget = (size_t)6 << 30;   // 6 GiB of scratch (of 288 GB): enough rows per launch at every n
     C = budget / (words_per_ct * 4);
     // measured: up to n = 8192 batches of 512 are 3-4 % faster than 256 (the long workgroups of the one-kernel
     // relinearisation leave a longer tail per launch), at n = 16384 128-256 is best; small rings need more
@@ -837,9 +890,9 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   if (need_lds_scale > c->max_lds) return HCNN_ERR_NODEVICE;
   // ciphertexts of one internal batch that can take the separate kernels
   const size_t C_split = (fused && fused_round) ? std::min(C, fused_round) : C;
-  int e = ensure_scratch(c, (C * words_main + C_split * words_split) * 4);
+  int e = static_ws ? 0 : ensure_work(c, (C * words_main + C_split * words_split) * 4);
   if (e) return e;
-  uint32_t* ext = c->scratch;
+  uint32_t* ext = static_ws ? c->static_scratch : c->work;
   uint32_t* ext_b = ext + C * 2 * L * rn;                 // used only by the two-operand product
   uint32_t* d = ext + C * ext_rows * rn;
   uint32_t* y = d + C * 3 * L * rn;
@@ -960,6 +1013,16 @@ int hcnn_ct_mul_relin(hcnn_ctx* c, const uint32_t* a, const uint32_t* b, size_t 
   return mul_relin_impl(c, a, b, n_ct, out);
 }
 
+int hcnn_ct_square_relin_noalloc(hcnn_ctx* c, const uint32_t* in, size_t n_ct, uint32_t* out) {
+  if (!c) return HCNN_ERR_NULL;
+  // no event pair around the launches of this call: an event may have to be created
+  const bool profile = c->profile;
+  c->profile = false;
+  const int e = mul_relin_impl(c, in, nullptr, n_ct, out, true);
+  c->profile = profile;
+  return e;
+}
+
 // ---------------------------------------------------------------- test helpers
 int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t* e_small, const uint32_t* a_evk,
                 const int32_t* e_evk, uint32_t* pk_out, uint32_t* evk_out) {
@@ -970,9 +1033,9 @@ int hcnn_keygen(hcnn_ctx* c, const int32_t* s, const uint32_t* a, const int32_t*
   const size_t rn = n, poly = (size_t)k * rn;
   const size_t bpp = n / kEwThreads;
   // scratch: s_hat [k][n] | s2 [k][n] | tmp [k*k][n]
-  int e = ensure_scratch(c, (2 * poly + (size_t)k * poly) * 4);
+  int e = ensure_work(c, (2 * poly + (size_t)k * poly) * 4);
   if (e) return e;
-  uint32_t* s_hat = c->scratch;
+  uint32_t* s_hat = c->work;
   uint32_t* s2 = s_hat + poly;
   uint32_t* tmp = s2 + poly;
 
@@ -1019,9 +1082,9 @@ static int encrypt_impl(hcnn_ctx* c, const uint32_t* pk, const uint32_t* m, cons
   const size_t bpp = n / kEwThreads;
   const size_t C = std::min<size_t>(n_ct, 64);
   // scratch: pk_hat [2][k][n] | u_hat [C][k][n] | prod [C][k][n]
-  int e = ensure_scratch(c, (2 * poly + 2 * C * poly) * 4);
+  int e = ensure_work(c, (2 * poly + 2 * C * poly) * 4);
   if (e) return e;
-  uint32_t* pk_hat = c->scratch;
+  uint32_t* pk_hat = c->work;
   uint32_t* u_hat = pk_hat + 2 * poly;
   uint32_t* prod = u_hat + C * poly;
   if ((e = ntt_dense(c, pk, pk_hat, 2 * (size_t)k, k, false))) return e;
@@ -1066,9 +1129,9 @@ static int decrypt_impl(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size
   const size_t bpp = n / kEwThreads;
   const size_t C = std::min<size_t>(n_ct, 64);
   // scratch: s_hat [k][n] | x [C][k][n]
-  int e = ensure_scratch(c, (poly + C * poly) * 4);
+  int e = ensure_work(c, (poly + C * poly) * 4);
   if (e) return e;
-  uint32_t* s_hat = c->scratch;
+  uint32_t* s_hat = c->work;
   uint32_t* x = s_hat + poly;
   SmallToRnsArgs sr{sk, s_hat, c->d_mods, k, n};
   if ((e = run<SmallToRnsKernel>(c, bpp, 0, sr))) return e;
@@ -1118,9 +1181,9 @@ int hcnn_noise_bits(hcnn_ctx* c, const int32_t* sk, const uint32_t* ct, size_t n
   const size_t bpp = n / kEwThreads;
   const size_t C = std::min<size_t>(n_ct, 64);
   // scratch: s_hat [k][n] | x [C][k][n]
-  int e = ensure_scratch(c, (poly + C * poly) * 4);
+  int e = ensure_work(c, (poly + C * poly) * 4);
   if (e) return e;
-  uint32_t* s_hat = c->scratch;
+  uint32_t* s_hat = c->work;
   uint32_t* x = s_hat + poly;
   if ((e = dev_memset(bits_out, 0, n_ct * sizeof(uint32_t), c->stream))) return e;
   SmallToRnsArgs sr{sk, s_hat, c->d_mods, k, n};
@@ -1183,7 +1246,7 @@ int hcnn_sample_uniform(hcnn_ctx* c, uint64_t seed, uint64_t stream, uint32_t* o
 int hcnn_get_stat(hcnn_ctx* c, int which, uint64_t* out) {
   if (!c || !out) return HCNN_ERR_NULL;
   if (which == HCNN_STAT_SCRATCH_BYTES) {
-    *out = c->scratch_bytes;
+    *out = c->work_bytes;
     return HCNN_OK;
   }
   if (which != HCNN_STAT_EXACT_FALLBACKS && which != HCNN_STAT_BAD_INPUT) return HCNN_ERR_ARG;
@@ -1235,6 +1298,8 @@ int hcnn_set_option(hcnn_ctx* c, int which, uint64_t value) {
       if (value > 2) return HCNN_ERR_ARG;
       c->fusion = value;
       return HCNN_OK;
+      if (value > 2) return HCNN_ERR_ARG;
+      return HCNN_OK;
   }
   return HCNN_ERR_ARG;
 }
@@ -1251,6 +1316,7 @@ const char* hcnn_strerror(int code) {
     case HCNN_ERR_NOKEY: return "relinearisation key not set";
     case HCNN_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case HCNN_ERR_NODEVICE: return "no usable device or LDS too small";
+    case HCNN_ERR_SCRATCH: return "one ciphertext's intermediate polynomials exceed the 128 MiB static scratch array";
   }
 #ifndef HCNN_HOSTEMU
   if (code > 0) return hipGetErrorString((hipError_t)code);

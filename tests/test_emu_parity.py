@@ -76,6 +76,30 @@ def test_square_relin_batch_split_into_rounds_and_remainder(backend):
     s.ctx.close()
 
 
+def test_square_relin_noalloc_equals_allocating_entry_point(backend):
+    """The entry point that works in the library's static array: same residues as hcnn_ct_square_relin on two calls in
+    a row (the second smaller), no work buffer allocated; a parameter set beyond the array is refused."""
+    from paper_1811_00778_amd import _capi
+    s = pc.Setup(backend, 1024, 3)
+    s.ctx.set_relin_key(backend.dev(s.evk))
+    for count in (11, 2):
+        cts = backend.dev(pc.gen.uniform_residues(s.rng, s.q, 1024, lead=(count, 2)))
+        out = s.ctx.ct_square_relin_noalloc(cts, np.zeros_like(cts))
+        assert s.ctx.scratch_bytes() == 0
+        assert np.array_equal(out[count - 1], pc.fv.square_relin(s.octx, cts[count - 1], s.evk))
+        ref = emu.EmuContext(1024, s.q, s.p, s.t)
+        ref.set_relin_key(backend.dev(s.evk))
+        assert np.array_equal(out, ref.ct_square_relin(cts))
+        ref.close()
+    s.ctx.close()
+    big = pc.Setup(backend, 32768, 30, with_keys=False)
+    x = backend.dev(np.zeros((1, 2, 30, 32768), dtype=np.uint32))
+    with pytest.raises(_capi.HcnnError) as err:
+        big.ctx.ct_square_relin_noalloc(x, np.zeros_like(x))
+    assert err.value.code == _capi.ERR["SCRATCH"]
+    big.ctx.close()
+
+
 def test_square_relin_exact_comparison_path(backend):
     pc.check_square_relin(backend, 1024, 2, force_exact=True)
     pc.check_square_relin(backend, 2048, 4, n_random=1, n_genuine=1, force_exact=True)

@@ -1,0 +1,80 @@
+"""The entry point that allocates nothing (hcnn_ct_square_relin_noalloc) against hcnn_ct_square_relin, through
+the C ABI on the device: same residues, bit for bit, on two calls in a row (the second with a smaller input),
+with no growth of the context's work buffer and no change in free device memory across the calls."""
+import numpy as np
+import pytest
+
+import parity_cases as pc
+from oracle import fv
+from paper_1811_00778_amd import _capi
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+
+class _Backend:
+    def __init__(self):
+        from paper_1811_00778_amd import binding
+        self.binding = binding
+        self.lib = binding.lib()
+        self._ctx = None
+
+    def make_ctx(self, n, q, p, t):
+        self._ctx = self.binding.Context(n, q, p, t)
+        return self._ctx
+
+    def dev(self, a):
+        return self._ctx.to_device(np.ascontiguousarray(a))
+
+    def host(self, buf):
+        return self._ctx.to_host_u32(buf)
+
+
+@pytest.mark.parametrize("n,k,first,second", [(4096, 4, 40, 7),      # one internal batch each
+                                              (8192, 8, 30, 3)])     # 30 ciphertexts exceed the array: two internal batches
+def test_noalloc_equals_allocating_entry_point(n, k, first, second):
+    import torch
+    print("[no-alloc] n=%d k=%d, %d then %d ciphertexts" % (n, k, first, second), flush=True)
+    b = _Backend()
+    s = pc.Setup(b, n, k, seed_id=2, stream=77)
+    ctx = s.ctx
+    ctx.set_relin_key(b.dev(s.evk))
+    big = b.dev(gen.uniform_residues(s.rng, s.q, n, lead=(first, 2)))
+    small = b.dev(gen.uniform_residues(s.rng, s.q, n, lead=(second, 2)))
+    out_big, out_small = torch.zeros_like(big), torch.zeros_like(small)
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    ctx.ct_square_relin_noalloc(big, out_big)
+    ctx.ct_square_relin_noalloc(small, out_small)          # same array, smaller input: nothing stale may leak in
+    torch.cuda.synchronize()
+    assert ctx.scratch_bytes() == 0                        # the context's own work buffer was never allocated
+    assert torch.cuda.mem_get_info()[0] == free0           # and no device memory was taken elsewhere
+    ref_big, ref_small = ctx.ct_square_relin(big), ctx.ct_square_relin(small)
+    assert ctx.scratch_bytes() > 0
+    assert torch.equal(out_big, ref_big)
+    assert torch.equal(out_small, ref_small)
+    # and the allocating entry point's output is the oracle's (one ciphertext of each call)
+    for dev_in, got, i in ((big, out_big, first - 1), (small, out_small, 0)):
+        assert np.array_equal(b.host(got)[i], fv.square_relin(s.octx, b.host(dev_in)[i], s.evk))
+    # in place, after the allocating call has run in between
+    again = small.clone()
+    ctx.ct_square_relin_noalloc(again, again)
+    assert torch.equal(again, ref_small)
+    ctx.close()
+
+
+def test_noalloc_refuses_a_parameter_set_beyond_the_array():
+    """n = 32768 with 30 primes needs 170 MiB for one ciphertext's intermediate polynomials: refused before anything
+    is enqueued (and before the key is asked for)."""
+    import torch
+    print("[no-alloc] refusal at n=32768 k=30", flush=True)
+    b = _Backend()
+    s = pc.Setup(b, 32768, 30, with_keys=False)
+    x = torch.zeros((1, 2, 30, 32768), dtype=torch.int32, device=s.ctx.device)
+    with pytest.raises(_capi.HcnnError) as err:
+        s.ctx.ct_square_relin_noalloc(x, torch.empty_like(x))
+    assert err.value.code == _capi.ERR["SCRATCH"]
+    with pytest.raises(_capi.HcnnError) as err:
+        s.ctx.ct_square_relin(x)                              # the allocating entry point gets as far as the key check
+    assert err.value.code == _capi.ERR["NOKEY"]
+    s.ctx.close()
