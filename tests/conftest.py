@@ -27,3 +27,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def progress(capsys):
+    """progress(msg): a line that reaches the terminal while the test is still running (output capture suspended
+    for it), for the long oracle computations of the full-size configurations."""
+    def emit(msg):
+        with capsys.disabled():
+            print("\n[progress] " + msg, flush=True)
+    return emit

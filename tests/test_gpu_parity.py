@@ -76,7 +76,7 @@ def test_square_relin_chunked_ragged(backend):
 
 def test_square_relin_largest_rings_residue_exact(backend):
     """Whole squarings at n = 16384 and n = 32768 against the oracle residue by residue; two primes keep the
-    oracle's O(n^2) products to seconds (the deep configurations themselves are checked through decryption)."""
+    oracle's O(n^2) products to seconds (the full-size configurations have tests of their own below)."""
     say("square_relin n=16384 k=2, n=32768 k=2 and k=6, every residue")
     pc.check_square_relin(backend, 16384, 2, n_random=1, n_genuine=1, check_decrypt=False)   # a 60-bit q has no room for the result's noise
     pc.check_square_relin(backend, 32768, 2, n_random=1, n_genuine=0)
@@ -84,22 +84,25 @@ def test_square_relin_largest_rings_residue_exact(backend):
 
 
 def test_square_relin_whole_rounds_plus_remainder(backend):
-    """A batch that the default policy splits: whole rounds of the one-kernel relinearisation, the rest through the
-    separate kernels.  Sampled ciphertexts against the oracle, every ciphertext against the two forced forms."""
-    say("square_relin n=4096 k=4, 259 ciphertexts: one round in one kernel + three through the separate kernels")
+    """A batch that the default policy splits: whole rounds of the one-kernel relinearisation (sized from the
+    occupancy that the runtime reports for the compiled kernel), the rest through the separate kernels.  Sampled
+    ciphertexts against the oracle, every ciphertext against the two forced forms."""
     n, k = 4096, 4
     s = pc.Setup(backend, n, k)
     s.ctx.set_relin_key(backend.dev(s.evk))
-    n_ct = 256 + 3                                         # one round of 1024 workgroups at k = 4, and three more
+    rnd = s.ctx.relin_fused_round()
+    say("square_relin n=4096 k=4: one round of %d ciphertexts in one kernel + three through the separate kernels" % rnd)
+    assert 8 <= rnd <= 2048
+    n_ct = rnd + 3
     cts = gen.uniform_residues(s.rng, s.q, n, lead=(n_ct, 2))
     dev = backend.dev(cts)
     s.ctx.set_profile(True)
     out = backend.host(s.ctx.ct_square_relin(dev))
     prof = s.ctx.profile()
-    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 256 * k * (k + 2)
+    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == rnd * k * (k + 2)
     assert prof["relin_mac"][0] == 1                       # three singles
     s.ctx.set_profile(False)
-    for i in (0, 131, 255, 256, 258):
+    for i in (0, rnd // 2 + 3, rnd - 1, rnd, rnd + 2):
         assert np.array_equal(out[i], fv.square_relin(s.octx, cts[i], s.evk)), i
     for mode in (1, 2):
         s.ctx.set_fusion(mode)
@@ -311,9 +314,10 @@ def _oracle_rows_check(name, got_row, want_row):
     assert np.array_equal(got_row, want_row), name
 
 
-def test_config2_full_batch_ntt_and_squarings(backend):
+def test_config2_full_batch_ntt_and_squarings(backend, progress):
     """n=8192, 8 primes, 64 random ciphertexts: transforms on the whole batch (sampled rows against the
-    oracle, round trip on everything), 64 squarings in one call (sampled ciphertexts against the oracle)."""
+    oracle, round trip on everything), 64 squarings in one call (six whole ciphertexts against the oracle,
+    residue by residue; every residue of all 64 canonical)."""
     cfg = gen.CONFIGS[2]
     n, k = cfg["n"], cfg["k"]
     say("config 2: setup")
@@ -330,11 +334,13 @@ def test_config2_full_batch_ntt_and_squarings(backend):
     say("config 2: 64 squarings on the GPU")
     s.ctx.set_relin_key(backend.dev(s.evk))
     out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
-    for i in (5, 63):
+    for l, p in enumerate(s.q):
+        assert int(out[:, :, l].max()) < p
+    for i in (0, 5, 21, 38, 50, 63):
         t0 = time.time()
         want = fv.square_relin(s.octx, cts[i], s.evk)
-        say("config 2: oracle squaring of ciphertext %d took %.1f s" % (i, time.time() - t0))
-        assert np.array_equal(out[i], want)
+        progress("config 2: oracle squaring of ciphertext %d took %.1f s" % (i, time.time() - t0))
+        assert np.array_equal(out[i], want), i
     s.ctx.close()
 
 
@@ -406,10 +412,10 @@ def _gpu_encrypt_random_plaintexts(backend, s, count, batch=256):
     return out, polys, er
 
 
-def test_config4_cifar_conv_layer(backend):
+def test_config4_cifar_conv_layer(backend, progress):
     """n=16384, 16 primes: 3072 encrypted inputs, 8 filters 3x3x3 stride 2 -> 1800 outputs, 1800 squarings.
-    Sampled MAC outputs and one whole squaring against the oracle; the decrypted result of another output
-    against the plain convolution squared."""
+    Sampled MAC outputs and four whole squarings against the oracle, residue by residue; the decrypted result
+    of another output against the plain convolution squared."""
     from paper_1811_00778_amd import layers
     cfg = gen.CONFIGS[4]
     n, k, t = cfg["n"], cfg["k"], cfg["t"]
@@ -453,19 +459,34 @@ def test_config4_cifar_conv_layer(backend):
     got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], backend.host(sq[f * G + g])), n, t)
     say("config 4: oracle decryption took %.1f s" % (time.time() - t0))
     assert np.array_equal(got.astype(np.int64), (acc % t) ** 2 % t)
-    # one whole squaring, residue for residue
-    o = 2 * G + 17
-    t0 = time.time()
-    want = fv.square_relin(s.octx, backend.host(flat[o]), s.evk)
-    say("config 4: oracle squaring took %.1f s" % (time.time() - t0))
-    assert np.array_equal(backend.host(sq[o]), want)
+    # four whole squarings (first and last output of the layer and two in between), residue for residue
+    for o in (0, 2 * G + 17, 5 * G + 101, F * G - 1):
+        t0 = time.time()
+        want = fv.square_relin(s.octx, backend.host(flat[o]), s.evk)
+        progress("config 4: oracle squaring of output %d took %.1f s" % (o, time.time() - t0))
+        assert np.array_equal(backend.host(sq[o]), want), o
     s.ctx.close()
 
 
-def test_config5_deep_modulus(backend):
+def _golden_square_hashes():
+    """{(name, b, l): sha256} of tests/golden/config5_square_sha256.txt (written by the oracle alone)."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config5_square_sha256.txt")
+    table = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, b, l, h = line.split()
+        table[(name, int(b), int(l))] = h
+    return table
+
+
+def test_config5_deep_modulus(backend, progress):
     """n=32768, 24 primes (26 auxiliary): 32 squarings with relinearisation and a 1024 -> 10 scalar MAC.
-    A whole squaring costs the oracle minutes here, so the squaring is checked through decryption
-    (oracle decrypt of the GPU result equals the slot-wise square); the MAC is compared residue for residue."""
+    Squarings: one ciphertext of random residues against the oracle run here, residue by residue; that and a
+    genuine one against the stored hashes of the oracle's output rows; the genuine one also through oracle
+    decryption (slot-wise square); every residue of all 32 canonical.  The MAC is compared residue for residue."""
+    import hashlib
     import torch
     from paper_1811_00778_amd import layers
     cfg = gen.CONFIGS[5]
@@ -484,11 +505,28 @@ def test_config5_deep_modulus(backend):
     batch = torch.cat([dgen, backend.dev(rnd)])
     say("config 5: 32 squarings")
     sq = s.ctx.ct_square_relin(batch)
+    hsq = backend.host(sq)
+    for l, p in enumerate(s.q):
+        assert int(hsq[:, :, l].max()) < p, ("canonical residues", l)
+    # stored hashes of the oracle's output rows (tests/golden/make_square_golden.py draws the same inputs)
+    golden = _golden_square_hashes()
+    for name, i in (("genuine", 1), ("random", 2 + 17)):
+        for b in range(2):
+            for l in range(k):
+                got = hashlib.sha256(np.ascontiguousarray(hsq[i, b, l], dtype="<u4").tobytes()).hexdigest()
+                assert got == golden[(name, b, l)], ("config 5 squaring row", name, b, l)
+    # the oracle itself, now, on another ciphertext of random residues
     t0 = time.time()
-    got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], backend.host(sq[1])), n, t)
+    progress("config 5: oracle squaring of one ciphertext (n = 32768, 24 primes) started")
+    want = fv.square_relin(s.octx, rnd[5], s.evk)
+    progress("config 5: oracle squaring took %.1f s" % (time.time() - t0))
+    assert np.array_equal(hsq[2 + 5], want)
+    t0 = time.time()
+    got = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], hsq[1]), n, t)
     say("config 5: oracle decryption took %.1f s" % (time.time() - t0))
     m = fv.slot_decode(polys[1], n, t).astype(np.uint64)
     assert np.array_equal(got, (m * m % t).astype(np.uint32))
+    del hsq
     # determinism across chunkings of the batch: same residues when squared four at a time
     s.ctx.set_square_chunk(4)
     sq4 = s.ctx.ct_square_relin(batch)
