@@ -2,6 +2,7 @@
 """Benchmark of the hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+    python bench.py --only ntt|square|mac-layer [...]      one operation alone, for profiler runs and size sweeps
 
 Workload ("primitive-8192"): n = 8192, q = 8 x 30-bit primes, t = 65537, a batch of 64
 ciphertexts of uniformly random residues resident in HBM.  One step is one pass of the
@@ -26,13 +27,27 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 ALU_PEAK_TOPS = 39.3           # 256 CU x 64 lanes x 2.4 GHz 32-bit integer VALU instructions / s
-RELIN_FUSED_TRAFFIC_RATIO = 1.703   # counted / algorithmic bytes of the one-kernel relinearisation at batch 64 (profiles/)
+HBM_COUNTER_PROFILE = os.path.join(ROOT, "profiles", "bench_primitive8192_hbm_counters.md")
 
 
-def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
+def counted_traffic(kernel_prefix):
+    """HBM bytes per launch that the FETCH_SIZE / WRITE_SIZE counters attribute to a kernel of this workload, as the
+    committed rocprofv3 summary records them (fetch KiB + write KiB of the table row whose kernel name starts with
+    `kernel_prefix`); None when the summary has no such row."""
+    try:
+        for line in open(HBM_COUNTER_PROFILE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 4 and cells[0].startswith(kernel_prefix):
+                return int((float(cells[2]) + float(cells[3])) * 1024)
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0, square=True):
     """One conv layer + square activation at the shape of configuration `cid`: ms for the scalar MAC,
-    ms for the squarings, compulsory-traffic bandwidth of the MAC.  Inputs are uniformly random residues
-    generated on the device (timing does not depend on the values)."""
+    ms for the squarings, compulsory-traffic bandwidth of the MAC.  Inputs are uniformly random canonical residues
+    drawn on the device by the library's counter-based sampler (timing does not depend on the values)."""
     cfg = gen.CONFIGS[cid]
     n, k, t = cfg["n"], cfg["k"], cfg["t"]
     fc = cfg.get("fc")
@@ -47,9 +62,7 @@ def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
     ctx.set_relin_key(evk)
     ctx.set_relin_order(relin_order)
     n_in = cv["c_in"] * cv["h"] * cv["w"]
-    gtorch = torch.Generator(device=ctx.device)
-    gtorch.manual_seed(gen.SEED_BASE + cid)
-    cts = torch.randint(0, 1 << 29, (n_in, 2, k, n), dtype=torch.int32, device=ctx.device, generator=gtorch)
+    cts = ctx.sample_uniform(gen.SEED_BASE + cid, 1, n_in * 2).reshape((n_in, 2, k, n))     # uniform below each q_l
     idx_h, _, (ho, wo) = layers.conv_index_table(cv["c_in"], cv["h"], cv["w"], cv["fh"], cv["fw"], cv["stride"])
     F, G = cv["filters"], idx_h.shape[0]
     w_h = layers.conv_weight_table(gen.int_weights(rng, (F, cv["c_in"], cv["fh"], cv["fw"]), cv["w_bound"]), G)
@@ -65,7 +78,8 @@ def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
         ev[0].record()
         ctx.ct_scalar_mac(cts, idx, w, cv["w_bound"], out=mac_out)
         ev[1].record()
-        ctx.ct_square_relin(flat, out=sq_out)
+        if square:
+            ctx.ct_square_relin(flat, out=sq_out)
         ev[2].record()
         torch.cuda.synchronize()
         if r:                                     # first repetition warms up (scratch allocation)
@@ -80,6 +94,61 @@ def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0):
                 mac_compulsory_GBps=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9, 1),
                 mac_hbm_frac=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 squarings=int(flat.shape[0]), squarings_per_s=round(flat.shape[0] / (sq * 1e-3), 1))
+
+
+def run_only(args, torch, binding, layers, gen):
+    """`--only`: one operation alone on random canonical residues, one line per operation (for profiler runs and
+    size sweeps; the JSON line of the benchmark is not printed)."""
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps          # ms per call
+
+    if args.only == "mac-layer":
+        cfg = dict(gen.CONFIGS[args.config])
+        if args.filters:
+            cfg["conv"] = dict(cfg["conv"], filters=args.filters)
+        saved = gen.CONFIGS[args.config]
+        gen.CONFIGS[args.config] = cfg
+        try:
+            print(json.dumps(time_layer(args.config, torch, binding, layers, gen, reps=args.reps, square=False)), flush=True)
+        finally:
+            gen.CONFIGS[args.config] = saved
+        return
+    n, k, t = args.n, args.k, args.t
+    q, p = binding.choose_moduli(n, k, t)
+    ctx = binding.Context(n, q, p, t)
+    if args.only == "ntt":
+        buf = ctx.sample_uniform(1811, 1, args.polys)
+        rows = args.polys * k
+        for name, fn in (("forward", ctx.ntt_fwd), ("inverse", ctx.ntt_inv)):
+            ms = timed(lambda: fn(buf), args.reps)
+            print("ntt %s n=%d rows=%d: %.1f us per call, %.2f ns per row, %.0f GB/s (read + write of every row)"
+                  % (name, n, rows, ms * 1e3, ms * 1e6 / rows, rows * n * 8 / ms / 1e6), flush=True)
+    else:
+        ctx.set_relin_key(ctx.sample_uniform(1811, 2, k * 2).reshape((k, 2, k, n)))     # random, not a genuine key
+        ctx.set_fusion(args.fusion)
+        cts = ctx.sample_uniform(1811, 3, args.cts * 2).reshape((args.cts, 2, k, n))
+        out = torch.empty_like(cts)
+        ms = timed(lambda: ctx.ct_square_relin(cts, out=out), args.reps)
+        print("square+relin n=%d k=%d k_aux=%d cts=%d: %.3f ms per call, %.0f squarings per second"
+              % (n, k, len(p), args.cts, ms, args.cts / ms * 1e3), flush=True)
+        ctx.reset_stats()
+        ctx.set_profile(True)
+        ctx.ct_square_relin(cts, out=out)
+        for name, (launches, blocks, tms) in ctx.profile().items():
+            if launches:
+                print("    %-12s %3d launches %9d blocks %8.3f ms  (%.2f ns per block)"
+                      % (name, launches, blocks, tms, tms * 1e6 / blocks), flush=True)
+        ctx.set_profile(False)
+    ctx.close()
 
 
 def time_primitives(n, k, torch, binding, gen, batch=64, reps=30):
@@ -164,10 +233,8 @@ def time_network(name, spec, in_shape, n, k, t, w_bound, torch, binding, network
     ctx.set_relin_key(evk)
     weights = [None if ws is None else gen.int_weights(rng, ws, w_bound) for ws in network.weight_shapes(spec, in_shape)]
     plan = network.Plan(spec, in_shape, weights, dev)
-    gtorch = torch.Generator(device=ctx.device)
-    gtorch.manual_seed(gen.SEED_BASE + 77)
     n_in = in_shape[0] * in_shape[1] * in_shape[2]
-    cts = torch.randint(0, 1 << 29, (n_in, 2, k, n), dtype=torch.int32, device=ctx.device, generator=gtorch)
+    cts = ctx.sample_uniform(gen.SEED_BASE + 77, 1, n_in * 2).reshape((n_in, 2, k, n))      # uniform below each q_l
     times = []
     for r in range(reps + 1):
         torch.cuda.synchronize()
@@ -205,6 +272,19 @@ def main():
     ap.add_argument("--no-networks", action="store_true", help="skip the whole-network timings")
     ap.add_argument("--no-primitives", action="store_true", help="skip the per-primitive latencies")
     ap.add_argument("--relin-order", type=int, default=0, help="HCNN_OPT_RELIN_ORDER (tuning experiments)")
+    ap.add_argument("--only", choices=("ntt", "square", "mac-layer"),
+                    help="time one operation alone and exit: ntt (--n --k --polys), square (--n --k --t --cts), "
+                         "mac-layer (--config 3|4|5 [--filters F])")
+    ap.add_argument("--n", type=int, default=8192)
+    ap.add_argument("--k", type=int, default=8)
+    ap.add_argument("--t", type=int, default=65537)
+    ap.add_argument("--polys", type=int, default=1024, help="--only ntt: polynomials of k limbs each")
+    ap.add_argument("--cts", type=int, default=1024, help="--only square: ciphertexts")
+    ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="--only mac-layer: configuration whose layer shape is used")
+    ap.add_argument("--filters", type=int, default=0, help="--only mac-layer: override the filter count")
+    ap.add_argument("--fusion", type=int, default=0, help="HCNN_OPT_FUSION (tuning experiments)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured streaming / instruction-issue ceilings")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain device copy of 256 MiB (a reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -217,6 +297,10 @@ def main():
     import torch
     from paper_1811_00778_amd import binding, layers
     from workloads import generators as gen
+
+    if args.only:
+        run_only(args, torch, binding, layers, gen)
+        return
 
     cfg = gen.CONFIGS[2]
     n, k, t, n_ct = cfg["n"], cfg["k"], cfg["t"], cfg["n_ct"]
@@ -251,8 +335,26 @@ def main():
         ref2.copy_(ref)
         torch.cuda.synchronize()
         del ref, ref2
+
+    # ---- warm-up: the W steps asked for, then on until the step time has settled (clocks and caches reach their
+    #      steady state after some tenths of a second, more than a handful of 0.3 ms steps): windows of 10 steps
+    #      until two in a row agree within 2 %, at least 0.3 s and at most 3 s in all
     for _ in range(args.warmup):
         step()
+    torch.cuda.synchronize()
+    warm_t0, prev, settle_steps = time.perf_counter(), None, 0
+    while True:
+        w0 = time.perf_counter()
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        window = time.perf_counter() - w0
+        settle_steps += 10
+        spent = time.perf_counter() - warm_t0
+        if spent > 3.0 or (spent >= 0.3 and prev is not None and abs(window - prev) <= 0.02 * prev):
+            break
+        prev = window
+
     # ---- timed region: exactly K steps, nothing else on the stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -280,78 +382,77 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     value = n_ct * args.steps / elapsed
 
-    # ---- per-kernel view and roofline of the dominant kernel
+    # ---- the device's own ceilings, measured now by the library's streaming and instruction-issue kernels
+    ceilings = None if args.no_ceilings else {name: round(v, 1) for name, v in ctx.measured_ceilings().items()}
+
+    # ---- per-kernel view; a roofline entry per kernel class, the one with the largest total time on top
     ct_bytes = 2 * k * n * 4
-    row_bytes = 2 * 4 * n                                  # one NTT row: read + write
+    row4 = 4 * n                                           # bytes of one row
+    L_ = k + len(p)
+    butterflies = (n // 2) * (n.bit_length() - 1)
     kernels = {}
     for name, (launches, blocks, ms) in prof.items():
         if launches:
             kernels[name] = dict(launches=launches, blocks=blocks, total_ms=round(ms, 4),
                                  avg_ms=round(ms / launches, 5), share=round(ms / (elapsed_prof * 1e3), 4))
+    # algorithmic HBM bytes of the launches of one step, per class (a plain row is read and written once; the three
+    # tensor components of a (ciphertext, limb) pair share two reads; the one-kernel relinearisation reads y and
+    # writes the result, the key comes from L2; the scalar MAC reads every input and writes every output once)
+    plain_rows = ntt_buf.numel() // n
+    step_bytes = {
+        "ntt_fwd": plain_rows * 2 * row4 + n_ct * 2 * L_ * 2 * row4,
+        "ntt_inv": plain_rows * 2 * row4 + n_ct * 5 * L_ * row4,
+        "relin_fused": n_ct * 5 * k * row4,
+        "scalar_mac": (n_ct + F * G) * ct_bytes,
+        "base_ext": n_ct * 2 * L_ * row4,
+        "scale": n_ct * 3 * (L_ + k) * row4,
+    }
+    profile_rows = {"ntt_fwd": "NttFwd<13, 5, 5>", "ntt_inv": "NttInv<13, 5, 2>", "relin_fused": "RelinFused",
+                    "scalar_mac": "Mac", "base_ext": "ExtKernelT", "scale": "ScaleKernelR"}
+
+    def class_roofline(name):
+        kd = kernels[name]
+        avg_s = kd["total_ms"] / kd["launches"] * 1e-3
+        per_step = kd["launches"] / args.steps
+        out = dict(kernel=name, avg_launch_ms=round(avg_s * 1e3, 5))
+        bytes_per_launch = step_bytes[name] / per_step if name in step_bytes else None
+        if name in ("ntt_fwd", "ntt_inv", "relin_fused", "tensor"):
+            # The transform is bound by integer VALU issue, not by HBM: a lazy butterfly needs 8 VALU instructions
+            # (3 multiplies, a 2-instruction conditional subtract, 3 add/sub), i.e. 8 * (n/2) * log2(n) per row =
+            # 6.5 instructions per byte moved, above the chip's balance of 39.3e12 / 8e12 = 4.9.  achieved =
+            # algorithmic instructions per launch / average launch time; `blocks` counts the transformed rows.
+            instr = kd["blocks"] / kd["launches"] * butterflies * 8
+            ach = instr / avg_s / 1e12
+            out.update(bound="alu", achieved=round(ach, 2), peak=ALU_PEAK_TOPS, unit="T int32 lane-instr/s",
+                       frac=round(ach / ALU_PEAK_TOPS, 4), algorithmic_instr_per_launch=int(instr))
+            if ceilings:
+                out["frac_of_measured_issue_rate"] = round(ach / ceilings["mul_lo_u32_Tops"], 4)
+        else:
+            out.update(bound="hbm", peak=HBM_PEAK_GBS, unit="GB/s")
+            if bytes_per_launch:
+                ach = bytes_per_launch / avg_s / 1e9
+                out.update(achieved=round(ach, 1), frac=round(ach / HBM_PEAK_GBS, 4))
+                if ceilings:
+                    out["frac_of_measured_copy_rate"] = round(ach / ceilings["copy_GBps"], 4)
+        if bytes_per_launch:
+            out.update(algorithmic_bytes_per_launch=int(bytes_per_launch),
+                       hbm_GBps=round(bytes_per_launch / avg_s / 1e9, 1),
+                       hbm_frac=round(bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, 4))
+        # HBM bytes that the FETCH_SIZE / WRITE_SIZE counters attribute to a launch of this kernel on this workload,
+        # as recorded in the committed rocprofv3 summary (None if it has no row for it)
+        out["traffic"] = counted_traffic(profile_rows.get(name, name))
+        out["traffic_source"] = "profiles/bench_primitive8192_hbm_counters.md" if out["traffic"] else None
+        return out
+
     roofline = None
     if kernels:
         dom = max(kernels, key=lambda kname: kernels[kname]["total_ms"])
-        kd = kernels[dom]
-        avg_s = kd["total_ms"] / kd["launches"] * 1e-3
-        if dom in ("ntt_fwd", "ntt_inv", "relin_fused"):
-            # The transform is bound by integer VALU issue, not by HBM: a lazy butterfly needs 8 VALU
-            # instructions (3 multiplies, a 2-instruction conditional subtract, 3 add/sub), i.e.
-            # 8 * (n/2) * log2(n) per row = 6.5 instructions per byte moved, above the chip's balance of
-            # 39.3e12 / 8e12 = 4.9.  achieved = algorithmic instructions per launch / average launch time.
-            rows_per_launch = kd["blocks"] / kd["launches"]
-            butterflies = (n // 2) * (n.bit_length() - 1)
-            instr_per_launch = rows_per_launch * butterflies * 8
-            ach = instr_per_launch / avg_s / 1e12
-            # Algorithmic HBM bytes of the class's three launches per step (a plain row is read and written once;
-            # the three tensor components of a (ciphertext, limb)
-            # pair share two reads, an adding store reads its addend too), and the bytes that the HBM counters
-            # attribute to them: ratios of counted to algorithmic bytes per kernel, measured with rocprofv3
-            # FETCH_SIZE / WRITE_SIZE on this workload (profiles/bench_primitive8192_hbm_counters.md).
-            L_ = k + len(p)
-            row4 = 4 * n
-            if dom == "ntt_fwd":
-                parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
-                         (n_ct * 2 * L_ * 2 * row4, 1.077)]                                 # extended operands
-            elif dom == "ntt_inv":
-                parts = [(ntt_buf.numel() // n * 2 * row4, 1.011),                          # plain rows
-                         (n_ct * 3 * L_ * row4 + n_ct * 2 * L_ * row4, 1.134),              # tensor-forming load
-                         (n_ct * 2 * k * 3 * row4, 1.008)]                                  # adding store
-            else:
-                # relinearisation in one kernel: reads y (3k rows per ciphertext), writes the result (2k rows);
-                # the key comes from L2.  `blocks` of this class counts transformed rows (k + 2 per workgroup).
-                parts = [(n_ct * 5 * k * row4, RELIN_FUSED_TRAFFIC_RATIO)]
-            per_step_launches = 1 if dom == "relin_fused" else (3 if dom == "ntt_inv" else 2)
-            bytes_per_launch = sum(b for b, _ in parts) / per_step_launches
-            traffic = sum(b * r for b, r in parts) / per_step_launches
-            roofline = dict(kernel=dom, bound="alu", achieved=round(ach, 2), peak=ALU_PEAK_TOPS,
-                            unit="T int32 lane-instr/s", frac=round(ach / ALU_PEAK_TOPS, 4), traffic=int(traffic),
-                            traffic_unit="HBM bytes per launch (counter ratios from profiles/bench_primitive8192_hbm_counters.md "
-                                         "applied to the algorithmic bytes)",
-                            algorithmic_instr_per_launch=int(instr_per_launch),
-                            algorithmic_bytes_per_launch=int(bytes_per_launch),
-                            hbm_GBps=round(bytes_per_launch / avg_s / 1e9, 1),
-                            hbm_frac=round(bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, 4),
-                            avg_launch_ms=round(avg_s * 1e3, 5))
-            # what the counters say of the same kernels (profiles/ntt_issue_counters.md): compiled VALU instructions
-            # per algorithmic butterfly instruction, and the share of all VALU issue slots the kernel fills at the
-            # clock the chip holds under this load (2.1-2.2 GHz, not the nominal 2.4 GHz of `peak`)
-            counters = {"ntt_fwd": (1.12, 0.84), "ntt_inv": (1.18, 0.81), "relin_fused": (1.26, 0.77)}[dom]
-            roofline["counters"] = dict(compiled_over_algorithmic_instr=counters[0], valu_issue_slot_use=counters[1],
-                                        source="profiles/ntt_issue_counters.md")
-        else:
-            roofline = dict(kernel=dom, bound="alu", achieved=None, peak=ALU_PEAK_TOPS, unit="T int32 lane-instr/s",
-                            frac=None, traffic=None, avg_launch_ms=round(avg_s * 1e3, 5))
-        # the two bandwidth targets, always reported
-        extra = {}
-        for kname in ("ntt_fwd", "ntt_inv"):
-            if kname in kernels:
-                kk_ = kernels[kname]
-                extra[kname + "_GBps"] = round(kk_["blocks"] * row_bytes / (kk_["total_ms"] * 1e-3) / 1e9, 1)
-        if "scalar_mac" in kernels:
-            kk_ = kernels["scalar_mac"]
-            mac_bytes = (n_ct + F * G) * ct_bytes          # every input once, every output once
-            extra["scalar_mac_GBps_compulsory"] = round(mac_bytes * kk_["launches"] / (kk_["total_ms"] * 1e-3) / 1e9, 1)
-        roofline["other_kernels"] = extra
+        roofline = class_roofline(dom)
+        roofline["classes"] = {name: class_roofline(name) for name in ("ntt_fwd", "ntt_inv", "scalar_mac", "relin_fused",
+                                                                       "scale", "base_ext") if name in kernels and name != dom}
+        # NTT launches of the step, time per row (the small launches of this batch fill one round of workgroups)
+        roofline["ntt_ns_per_row"] = {name: round(kernels[name]["total_ms"] * 1e6 / kernels[name]["blocks"], 2)
+                                      for name in ("ntt_fwd", "ntt_inv") if name in kernels}
 
     # ---- the layer-shaped workloads of the metric ("encrypted conv layer ms"): scalar MAC + square
     #      activation on MNIST- and CIFAR-10-shaped layers, random ciphertexts resident in HBM
@@ -404,6 +505,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settling_steps_after_warmup": settle_steps,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -415,6 +517,7 @@ def main():
                                "+ 64 squarings with relinearisation",
                    "n": n, "k": k, "k_aux": len(p), "batch": n_ct},
         "roofline": roofline,
+        "measured_ceilings": ceilings,
         "cpu_baseline": cpu,
         "conv_layers": layers_out,
         "networks": networks_out,

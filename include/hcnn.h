@@ -230,7 +230,13 @@ enum {
   HCNN_STAT_EXACT_FALLBACKS = 0, /* coefficients whose base conversion needed the exact
                                     mixed-radix comparison instead of the fixed-point estimate */
   HCNN_STAT_BAD_INPUT = 1,       /* out-of-range indices / weights seen by hcnn_ct_scalar_mac   */
-  HCNN_STAT_SCRATCH_BYTES = 2    /* device scratch currently held by the context               */
+  HCNN_STAT_SCRATCH_BYTES = 2,   /* device work buffer currently held by the context            */
+  HCNN_STAT_RELIN_FUSED_WGS = 3, /* workgroups of the one-kernel relinearisation that the device holds at a time
+                                    (compute units x the occupancy the runtime reports for the compiled kernel);
+                                    the default policy of HCNN_OPT_FUSION sizes its rounds from it: a round is
+                                    8 * floor(this / 8 / k) ciphertexts                         */
+  HCNN_STAT_TENSOR_FUSED_WGS = 4 /* the same for the one-kernel squaring tensor, taken for internal batches of
+                                    at least 6 * this (ciphertext, limb) pairs                  */
 };
 /* Synchronises the context's stream, then reads the counter. */
 int hcnn_get_stat(hcnn_ctx* ctx, int which, uint64_t* out);
@@ -287,6 +293,21 @@ enum {
 };
 int hcnn_profile_read(hcnn_ctx* ctx, int kernel_class, uint64_t* launches, uint64_t* blocks,
                       double* total_ms);
+
+/* Measured ceilings of the device the context lives on, for reading the timings above against: the rate that a
+ * plain streaming kernel of this library reaches on 512 MiB buffers (HCNN_CEIL_COPY: bytes read + bytes written
+ * per second of a device-to-device copy; _READ: a read-only pass; _WRITE: a fill), and the issue rate of the
+ * integer instructions that the transforms (32-bit low / high multiply, add) and the multiply-accumulate (32 x 32
+ * + 64-bit multiply-add, unsigned and signed) are made of, eight independent chains per lane at full occupancy.
+ * value_out: GB/s for the three streaming cases, 10^12 lane-instructions per second for the others.
+ * Allocates and frees its own buffers, launches on the context's stream and synchronises it: a diagnostic, not
+ * for the hot path. */
+enum {
+  HCNN_CEIL_COPY = 0, HCNN_CEIL_READ = 1, HCNN_CEIL_WRITE = 2,
+  HCNN_CEIL_MUL_LO = 3, HCNN_CEIL_MUL_HI = 4, HCNN_CEIL_MAD_U64 = 5, HCNN_CEIL_MAD_I64 = 6, HCNN_CEIL_ADD = 7,
+  HCNN_CEIL_COUNT = 8
+};
+int hcnn_measure_ceiling(hcnn_ctx* ctx, int which, double* value_out);
 
 const char* hcnn_strerror(int code);
 

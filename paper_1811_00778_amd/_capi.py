@@ -6,10 +6,12 @@ u64p = C.POINTER(C.c_uint64)
 ptr = C.c_void_p
 
 ERR = dict(OK=0, NULL=-1, N=-2, PRIME=-3, T=-4, AUX=-5, ARG=-6, NOKEY=-7, ALIGN=-8, NODEVICE=-9, SCRATCH=-10)
-STAT_EXACT_FALLBACKS, STAT_BAD_INPUT, STAT_SCRATCH_BYTES = 0, 1, 2
+STAT_EXACT_FALLBACKS, STAT_BAD_INPUT, STAT_SCRATCH_BYTES, STAT_RELIN_FUSED_WGS, STAT_TENSOR_FUSED_WGS = 0, 1, 2, 3, 4
 OPT_AMBIGUITY_BAND, OPT_SQUARE_CHUNK, OPT_PROFILE, OPT_RELIN_ORDER, OPT_FUSION = 0, 1, 2, 3, 4
 PROF_CLASSES = ["ntt_fwd", "ntt_inv", "base_ext", "tensor", "scale", "digit", "relin_mac", "relin_add",
                 "scalar_mac", "other", "relin_fused"]
+CEILINGS = ["copy_GBps", "read_GBps", "write_GBps", "mul_lo_u32_Tops", "mul_hi_u32_Tops", "mad_u64_u32_Tops",
+            "mad_i64_i32_Tops", "add_u32_Tops"]
 MAX_LIMBS, MAX_FILTERS = 32, 16
 
 # name -> argtypes; every entry point returns int except hcnn_strerror
@@ -39,6 +41,7 @@ SIGNATURES = {
     "hcnn_reset_stats": [ptr],
     "hcnn_set_option": [ptr, C.c_int, C.c_uint64],
     "hcnn_profile_read": [ptr, C.c_int, u64p, u64p, C.POINTER(C.c_double)],
+    "hcnn_measure_ceiling": [ptr, C.c_int, C.POINTER(C.c_double)],
     "hcnn_strerror": [C.c_int],
 }
 
@@ -118,6 +121,15 @@ class RawContext:
             a, b, ms = C.c_uint64(0), C.c_uint64(0), C.c_double(0.0)
             check(self.lib, self.lib.hcnn_profile_read(self.handle, cls, C.byref(a), C.byref(b), C.byref(ms)))
             out[name] = (int(a.value), int(b.value), float(ms.value))
+        return out
+
+    def ceilings(self):
+        """{name: value} of hcnn_measure_ceiling: GB/s for the streaming kernels, 10^12 lane-instructions/s else."""
+        out = {}
+        for which, name in enumerate(CEILINGS):
+            v = C.c_double(0.0)
+            check(self.lib, self.lib.hcnn_measure_ceiling(self.handle, which, C.byref(v)))
+            out[name] = float(v.value)
         return out
 
     def set_option(self, which, value):

@@ -56,14 +56,27 @@ class Context(OpsMixin):
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         stream = torch.cuda.current_stream(self.device).cuda_stream
+        self._stream = stream
         self.raw = _capi.RawContext(lib(), n, q_primes, p_primes, t, stream)
 
     def use_stream(self, stream=None):
         """Launch on `stream` (a torch.cuda.Stream; default: torch's current stream) from now on
-        (hcnn_set_stream).  After one warm-up call per operation and size, the hot-path calls allocate nothing
-        and enqueue kernels only, so they can be recorded into a HIP graph on the stream given here."""
+        (hcnn_set_stream; the library waits for the work it has enqueued on the old stream first).  After one
+        warm-up call per operation and size, the hot-path calls allocate nothing and enqueue kernels only, so they
+        can be recorded into a HIP graph on the stream given here.
+
+        Rule: the context's stream must be torch's current stream whenever an operation is called.  Output
+        tensors come from torch's allocator, which hands a freed block out again to later work on the stream it
+        was allocated on; if the library launched on another stream, that work could overwrite a buffer the
+        library's kernels still use.  Every call checks this and raises instead."""
         stream = torch.cuda.current_stream(self.device) if stream is None else stream
         self.raw.call("hcnn_set_stream", ctypes.c_void_p(stream.cuda_stream))
+        self._stream = stream.cuda_stream
+
+    def _pre_call(self):
+        if torch.cuda.current_stream(self.device).cuda_stream != self._stream:
+            raise RuntimeError("the context is bound to another HIP stream than torch's current one: call "
+                               "use_stream() inside the `with torch.cuda.stream(...)` block (and again after it)")
 
     def _ptr(self, x):
         return ctypes.c_void_p(x.data_ptr())

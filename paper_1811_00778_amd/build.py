@@ -7,7 +7,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libhcnn.so")
 SOURCES = [os.path.join(CSRC, "hcnn.cpp")]
-HEADERS = [os.path.join(CSRC, h) for h in ("platform.h", "modarith.h", "ntt_kernels.h", "fv_kernels.h")]
+HEADERS = [os.path.join(CSRC, h) for h in ("platform.h", "modarith.h", "ntt_kernels.h", "fv_kernels.h", "rate_kernels.h")]
 HEADERS.append(os.path.join(os.path.dirname(_HERE), "include", "hcnn.h"))
 
 HIPCC_FLAGS = [

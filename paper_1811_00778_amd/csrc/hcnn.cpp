@@ -10,6 +10,7 @@
 
 #include "fv_kernels.h"
 #include "ntt_kernels.h"
+#include "rate_kernels.h"
 
 using namespace hcnn;
 
@@ -295,6 +296,7 @@ struct hcnn_ctx {
   uint64_t fusion = 0;   // one-kernel tensor / relinearisation: 0 = chosen per batch, 1 = never, 2 = always where available
   size_t max_lds = 0;
   uint32_t compute_units = 256;
+  uint32_t relin_fused_wgs = 1, tensor_fused_wgs = 1;   // resident workgroups per compute unit of the one-kernel forms
 
   // optional per-kernel timing (HCNN_OPT_PROFILE): an event pair around every launch
   struct Pending { int cls; uint64_t blocks; hcnn_event_t start, stop; };
@@ -348,16 +350,17 @@ int take_event(hcnn_ctx* c, hcnn_event_t* ev) {
 // `units` (default: the grid) is what the profile counts: the rows of an NTT launch whose grid is padded.
 template <class K, class Args>
 int run(hcnn_ctx* c, size_t grid, size_t lds_bytes, const Args& a, size_t units = 0) {
-  if (!c->profile || grid == 0) return launch<K>(c->stream, grid, lds_bytes, a);
+  const hcnn_stream_t stream = c->stream;
+  if (!c->profile || grid == 0) return launch<K>(stream, grid, lds_bytes, a);
   hcnn_ctx::Pending pd;
   pd.cls = KernelClass<K>::id;
   pd.blocks = units ? units : grid;
   int e;
   if ((e = take_event(c, &pd.start))) return e;
   if ((e = take_event(c, &pd.stop))) return e;
-  if ((e = event_record(pd.start, c->stream))) return e;
-  if ((e = launch<K>(c->stream, grid, lds_bytes, a))) return e;
-  if ((e = event_record(pd.stop, c->stream))) return e;
+  if ((e = event_record(pd.start, stream))) return e;
+  if ((e = launch<K>(stream, grid, lds_bytes, a))) return e;
+  if ((e = event_record(pd.stop, stream))) return e;
   c->pending.push_back(pd);
   return 0;
 }
@@ -675,6 +678,66 @@ int mac_dispatch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
   return HCNN_ERR_ARG;
 }
 
+// Occupancy of the two long-running one-kernel forms for this ring and basis, asked of the runtime once.
+int query_fused_occupancy(hcnn_ctx* c) {
+  if (c->logn > 14) return 0;                       // neither form exists for the largest ring
+  const uint32_t k = c->k;
+  int e = 0, r = 1, t = 1;
+#define HCNN_OCC(LOGN, LOGR)                                                                                          \
+  {                                                                                                                   \
+    const size_t lds = NttGeom<LOGN, LOGR>::kLdsBytes;                                                                \
+    e = k <= 8    ? resident_workgroups_per_cu<RelinFused<LOGN, LOGR, kNttFusedMac>, RelinFusedArgs>(lds, &r)         \
+        : k <= 16 ? resident_workgroups_per_cu<RelinFused<LOGN, LOGR, kNttFusedMac16>, RelinFusedArgs>(lds, &r)       \
+                  : resident_workgroups_per_cu<RelinFused<LOGN, LOGR, kNttFusedMacAny>, RelinFusedArgs>(lds, &r);     \
+  }
+  switch (c->logn) {
+    case 10: HCNN_OCC(10, 4) break;
+    case 11: HCNN_OCC(11, 4) break;
+    case 12: HCNN_OCC(12, 4) break;
+    case 13: HCNN_OCC(13, 5) break;
+    case 14: HCNN_OCC(14, 4) break;
+  }
+#undef HCNN_OCC
+  if (e) return e;
+  switch (c->logn) {
+    case 10: e = resident_workgroups_per_cu<TensorFused<10, 4>, TensorFusedArgs>(NttGeom<10, 4>::kLdsBytes, &t); break;
+    case 11: e = resident_workgroups_per_cu<TensorFused<11, 4>, TensorFusedArgs>(NttGeom<11, 4>::kLdsBytes, &t); break;
+    case 12: e = resident_workgroups_per_cu<TensorFused<12, 4>, TensorFusedArgs>(NttGeom<12, 4>::kLdsBytes, &t); break;
+    case 13: e = resident_workgroups_per_cu<TensorFused<13, 4>, TensorFusedArgs>(NttGeom<13, 4>::kLdsBytes, &t); break;
+    case 14: e = resident_workgroups_per_cu<TensorFused<14, 4>, TensorFusedArgs>(NttGeom<14, 4>::kLdsBytes, &t); break;
+  }
+  if (e) return e;
+  c->relin_fused_wgs = (uint32_t)r;
+  c->tensor_fused_wgs = (uint32_t)t;
+  return 0;
+}
+
+// Median duration in milliseconds of `reps` launches of one kernel on the context's stream, one event pair each.
+template <class K, class Args>
+int timed_launches(hcnn_ctx* c, size_t grid, const Args& a, int reps, double* ms_out) {
+  hcnn_event_t e0, e1;
+  int e;
+  if ((e = event_create(&e0))) return e;
+  if ((e = event_create(&e1))) { event_destroy(e0); return e; }
+  std::vector<float> ms;
+  e = launch<K>(c->stream, grid, 0, a);                     // warm-up
+  for (int r = 0; r < reps && !e; ++r) {
+    float t = 0.f;
+    if ((e = event_record(e0, c->stream))) break;
+    if ((e = launch<K>(c->stream, grid, 0, a))) break;
+    if ((e = event_record(e1, c->stream))) break;
+    if ((e = stream_sync(c->stream))) break;
+    if ((e = event_elapsed_ms(&t, e0, e1))) break;
+    ms.push_back(t);
+  }
+  event_destroy(e0);
+  event_destroy(e1);
+  if (e) return e;
+  std::sort(ms.begin(), ms.end());
+  *ms_out = ms[ms.size() / 2];
+  return 0;
+}
+
 }  // namespace
 
 // ================================================================= C ABI
@@ -743,6 +806,7 @@ int hcnn_ctx_create(hcnn_ctx** out, uint32_t n, uint32_t k, const uint32_t* q, u
   }
   e = build_tables(c);
   if (!e) e = static_scratch_of_current_device(&c->static_scratch);
+  if (!e) e = query_fused_occupancy(c);
   if (e) {
     hcnn_ctx_destroy(c);
     return e;
@@ -832,17 +896,13 @@ int hcnn_ct_scalar_mac(hcnn_ctx* c, const uint32_t* in, size_t n_in, const uint3
   return mac_dispatch(c, G * tiles, a);
 }
 
-// HMult of Sec. 2.1 on n_ct pairs (a_i, b_i); b == nullptr squares a (HSquare).
-// Workgroups of the one-kernel relinearisation that the device holds at a time (the one-kernel squaring tensor,
-// with 16 waves per compute unit at every size it is used for, holds the same numbers): its register use allows
-// 8 waves per compute unit at n = 8192 (213 registers, 32 residues per thread, 4 waves per workgroup) and 16 at the
-// other sizes (at most 128 registers, 16 residues per thread).
-static size_t relin_fused_slots(const hcnn_ctx* c) {
-  const size_t waves_per_wg = std::max<size_t>(1, ((size_t)1 << c->logn) / (c->logn == 13 ? 32 : 16) / 64);
-  const size_t waves_per_cu = c->logn == 13 ? 8 : 16;
-  return (size_t)c->compute_units * (waves_per_cu / waves_per_wg);
-}
+// Workgroups of the one-kernel relinearisation / of the one-kernel squaring tensor that the device holds at a time:
+// compute units x the per-compute-unit figure that the runtime reported for the compiled kernel when the context
+// was created (query_fused_occupancy).  The rounds of these long-running kernels are sized from it.
+static size_t relin_fused_slots(const hcnn_ctx* c) { return (size_t)c->compute_units * c->relin_fused_wgs; }
+static size_t tensor_fused_slots(const hcnn_ctx* c) { return (size_t)c->compute_units * c->tensor_fused_wgs; }
 
+// HMult of Sec. 2.1 on n_ct pairs (a_i, b_i); b == nullptr squares a (HSquare).
 // static_ws: the intermediate polynomials go to this device's copy of the file-scope array `scratch` and nothing is
 // allocated; a parameter set whose single ciphertext does not fit that array is refused.
 static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b, size_t n_ct, uint32_t* out,
@@ -890,7 +950,8 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   if (need_lds_scale > c->max_lds) return HCNN_ERR_NODEVICE;
   // ciphertexts of one internal batch that can take the separate kernels
   const size_t C_split = (fused && fused_round) ? std::min(C, fused_round) : C;
-  int e = static_ws ? 0 : ensure_work(c, (C * words_main + C_split * words_split) * 4);
+  int e;
+  e = static_ws ? 0 : ensure_work(c, (C * words_main + C_split * words_split) * 4);
   if (e) return e;
   uint32_t* ext = static_ws ? c->static_scratch : c->work;
   uint32_t* ext_b = ext + C * 2 * L * rn;                 // used only by the two-operand product
@@ -902,21 +963,45 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
   const size_t bpp = n / kEwThreads;                 // blocks per polynomial, 1 coefficient / thread
   const size_t bpr = n / (kEwThreads * kEwVec);      // blocks per row, 4 coefficients / thread
 
-  for (size_t c0 = 0; c0 < n_ct; c0 += C) {
-    const size_t cc = std::min(C, n_ct - c0);
+  // How many ciphertexts of an internal batch of cc take the one-kernel relinearisation (steps 6-8 in one kernel
+  // for whole rounds of its workgroups: a row and its two 64-bit sums stay in registers).
+  auto fused_count = [&](size_t cc) -> size_t {
+    size_t nf = 0;
+    if (fused && fused_round) {
+      nf = cc / fused_round * fused_round;
+      // a last round joins when it is at least 3/8 full (3/4 if it is the only one): measured break-even points
+      const size_t rest = cc - nf;
+      if (nf ? rest * 8 >= fused_round * 3 : rest * 4 >= fused_round * 3) nf = cc;
+      if (c->fusion == 2) nf = cc;
+    }
+    return nf;
+  };
+  // Steps 2+3 in one kernel for squarings: its workgroups are long (five transforms) and two fit a compute unit at
+  // n = 8192 (one at n = 16384), so it pays from several rounds of workgroups on (measured: +3-5 % from 6 rounds,
+  // nothing below).
+  auto takes_tensor_fused = [&](size_t cc) {
+    return !in_b && c->logn <= 14 && c->fusion != 1 && (c->fusion == 2 || cc * L >= 6 * tensor_fused_slots(c));
+  };
+
+  // One internal batch: ciphertexts [c0, c0 + cc) of the call, kept in slots [s0, s0 + cc) of the work arrays, nf of
+  // them through the one-kernel relinearisation.
+  auto one_batch = [&](size_t c0, size_t cc, size_t s0, size_t nf) -> int {
+    int e;
+    uint32_t* const b_ext = ext + s0 * 2 * L * rn;
+    uint32_t* const b_ext_b = ext_b + s0 * 2 * L * rn;
+    uint32_t* const b_d = d + s0 * 3 * L * rn;
+    uint32_t* const b_y = y + s0 * 3 * k * rn;
+    uint32_t* const b_dig = dig + s0 * k * k * rn;
+    uint32_t* const b_acc = acc + s0 * 2 * k * rn;
     // 1. centred lift of c0, c1 extended to the auxiliary primes (only the new rows are written);
     // 2. forward NTT over all k + k' limbs, the first k read from the ciphertext itself
     ExtArgs ea;
-    ea.in = in + c0 * ct_words; ea.out = ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
+    ea.in = in + c0 * ct_words; ea.out = b_ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-    // 2+3 in one kernel for squarings: its workgroups are long (five transforms) and two fit a compute unit at
-    // n = 8192 (one at n = 16384), so it pays from several rounds of workgroups on (measured: +3-5 % from 6 rounds,
-    // nothing below)
-    const bool tensor_fused = !in_b && c->logn <= 14 && c->fusion != 1 &&
-                              (c->fusion == 2 || cc * L >= 6 * relin_fused_slots(c));
+    const bool tensor_fused = takes_tensor_fused(cc);
     if (tensor_fused) {
-      TensorFusedArgs ta{in + c0 * ct_words, ext, d, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, L, (uint32_t)(cc * L)};
+      TensorFusedArgs ta{in + c0 * ct_words, b_ext, b_d, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, L, (uint32_t)(cc * L)};
       const size_t rows = cc * L * 5;
       switch (c->logn) {
         case 10: e = run<TensorFused<10, 4>>(c, cc * L, NttGeom<10, 4>::kLdsBytes, ta, rows); break;
@@ -929,35 +1014,28 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
         default: e = HCNN_ERR_N; break;
       }
       if (e) return e;
-    } else
-    if ((e = ntt_dense(c, ext, ext, cc * 2 * L, L, false, kNttStoreLazy, in + c0 * ct_words, k))) return e;
+    } else if ((e = ntt_dense(c, b_ext, b_ext, cc * 2 * L, L, false, kNttStoreLazy, in + c0 * ct_words, k))) {
+      return e;
+    }
     if (in_b) {
-      ea.in = in_b + c0 * ct_words; ea.out = ext_b;
+      ea.in = in_b + c0 * ct_words; ea.out = b_ext_b;
       if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-      if ((e = ntt_dense(c, ext_b, ext_b, cc * 2 * L, L, false, kNttStoreLazy, in_b + c0 * ct_words, k))) return e;
+      if ((e = ntt_dense(c, b_ext_b, b_ext_b, cc * 2 * L, L, false, kNttStoreLazy, in_b + c0 * ct_words, k))) return e;
     }
     // 3+4. tensor formed while loading, then back to coefficients: the integer tensor, known mod q*p
     if (in_b) {
-      if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensorMul, ext_b))) return e;
+      if ((e = ntt_dense(c, b_ext, b_d, cc * 3 * L, L, true, kNttLoadTensorMul, b_ext_b))) return e;
     } else if (!tensor_fused) {
-      if ((e = ntt_dense(c, ext, d, cc * 3 * L, L, true, kNttLoadTensor))) return e;
+      if ((e = ntt_dense(c, b_ext, b_d, cc * 3 * L, L, true, kNttLoadTensor))) return e;
     }
     // 5. y = round(t/q * d) mod q
     ScaleArgs sa;
-    sa.d = d; sa.y = y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
+    sa.d = b_d; sa.y = b_y; sa.to_p = c->to_p; sa.to_q = c->to_q; sa.tq_inv = c->d_tq_inv; sa.n = n;
     sa.band = c->band; sa.fallback_counter = c->d_counters;
     if ((e = scale_dispatch(c, cc * 3 * bpp, sa))) return e;
-    // 6-8 in one kernel for whole rounds of its workgroups (a row and its two 64-bit sums stay in registers)
-    size_t nf = 0;
-    if (fused && fused_round) {
-      nf = cc / fused_round * fused_round;
-      // a last round joins when it is at least 3/8 full (3/4 if it is the only one): measured break-even points
-      const size_t rest = cc - nf;
-      if (nf ? rest * 8 >= fused_round * 3 : rest * 4 >= fused_round * 3) nf = cc;
-      if (c->fusion == 2) nf = cc;
-    }
+    // 6-8 in one kernel
     if (nf) {
-      RelinFusedArgs fa{y, c->d_evk_hat, out + c0 * ct_words, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, (uint32_t)(nf * k)};
+      RelinFusedArgs fa{b_y, c->d_evk_hat, out + c0 * ct_words, c->d_tw_fwd, c->d_tw_inv, c->d_limbs, k, (uint32_t)(nf * k)};
       const size_t grid = ntt_grouped_grid(nf * k, k), rows = nf * k * (k + 2);
 #define HCNN_FUSED(LOGN, LOGR)                                                                                      \
   (k <= 8 ? run<RelinFused<LOGN, LOGR, kNttFusedMac>>(c, grid, NttGeom<LOGN, LOGR>::kLdsBytes, fa, rows)             \
@@ -975,14 +1053,14 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
       if (e) return e;
     }
     const size_t ns = cc - nf;                                // ciphertexts left for the separate kernels
-    if (ns == 0) continue;
-    const uint32_t* y_s = y + nf * 3 * k * rn;
+    if (ns == 0) return 0;
+    const uint32_t* y_s = b_y + nf * 3 * k * rn;
     uint32_t* out_s = out + (c0 + nf) * ct_words;
     // 6. RNS digits of y2, each reduced modulo every q_j while loading, transformed
-    if ((e = ntt_dense(c, y_s, dig, ns * k * k, k, false, kNttLoadDigit))) return e;
+    if ((e = ntt_dense(c, y_s, b_dig, ns * k * k, k, false, kNttLoadDigit))) return e;
     // 7. inner product with the evaluation key
     RelinMacArgs ra;
-    ra.dig = dig; ra.evk = c->d_evk_hat; ra.acc = acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
+    ra.dig = b_dig; ra.evk = c->d_evk_hat; ra.acc = b_acc; ra.mods = c->d_mods; ra.k = k; ra.n = n;
     // in the plain (ciphertext-major) order every die touches the key tiles of all limbs: 2*k*k*(tiles/8) * 4 KiB
     ra.key_major = (bpr % kXcds == 0 && (size_t)2 * k * k * (bpr / kXcds) * 4096 > ((size_t)1 << 20)) ? 1u : 0u;
     if (c->relin_order == 1) ra.key_major = 0;
@@ -999,7 +1077,13 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
       if ((e = run<RelinMacKernel<1>>(c, (ns % kRelinCts) * k * bpr, 0, ra))) return e;
     }
     // 8. c'_b = y_b + sum_i evk[i][b] * digit_i : inverse transform with the addition on the way out
-    if ((e = ntt_dense(c, acc, out_s, ns * 2 * k, k, true, kNttStoreAdd, y_s))) return e;
+    return ntt_dense(c, b_acc, out_s, ns * 2 * k, k, true, kNttStoreAdd, y_s);
+  };
+
+  for (size_t c0 = 0; c0 < n_ct; c0 += C) {
+    const size_t cc = std::min(C, n_ct - c0);
+    const size_t nf = fused_count(cc);
+    if ((e = one_batch(c0, cc, 0, nf))) return e;
   }
   return HCNN_OK;
 }
@@ -1249,11 +1333,60 @@ int hcnn_get_stat(hcnn_ctx* c, int which, uint64_t* out) {
     *out = c->work_bytes;
     return HCNN_OK;
   }
+  if (which == HCNN_STAT_RELIN_FUSED_WGS || which == HCNN_STAT_TENSOR_FUSED_WGS) {
+    *out = which == HCNN_STAT_RELIN_FUSED_WGS ? relin_fused_slots(c) : tensor_fused_slots(c);
+    return HCNN_OK;
+  }
   if (which != HCNN_STAT_EXACT_FALLBACKS && which != HCNN_STAT_BAD_INPUT) return HCNN_ERR_ARG;
   unsigned long long v[2] = {0, 0};
   int e = copy_d2h(v, c->d_counters, sizeof(v), c->stream);
   if (e) return e;
   *out = v[which];
+  return HCNN_OK;
+}
+
+int hcnn_measure_ceiling(hcnn_ctx* c, int which, double* value_out) {
+  if (!c || !value_out) return HCNN_ERR_NULL;
+  if (which < 0 || which >= HCNN_CEIL_COUNT) return HCNN_ERR_ARG;
+  int e;
+  double ms = 0.0;
+  if (which <= HCNN_CEIL_WRITE) {
+    const size_t bytes = (size_t)512 << 20;                                       // per buffer
+    const size_t grid = bytes / ((size_t)kRateThreads * kStreamUnroll * 16);
+    void* src = nullptr;
+    void* dst = nullptr;
+    if ((e = dev_malloc(&src, bytes))) return e;
+    if ((e = dev_malloc(&dst, bytes))) { dev_free(src); return e; }
+    StreamArgs a;
+    a.src = (const U4*)src; a.dst = (U4*)dst; a.fill = 0x01010101u;
+    a.mode = 2;                                                                  // defined contents for both buffers
+    e = launch<StreamKernel>(c->stream, grid, 0, a);
+    if (!e) { a.dst = (U4*)src; e = launch<StreamKernel>(c->stream, grid, 0, a); a.dst = (U4*)dst; }
+    a.mode = which == HCNN_CEIL_COPY ? 0u : (which == HCNN_CEIL_READ ? 1u : 2u);
+    a.fill = 0x5a5a5a5au;                              // read mode: the xor of equal words is 0, never this
+    if (!e) e = timed_launches<StreamKernel>(c, grid, a, 9, &ms);
+    const int es = stream_sync(c->stream);
+    dev_free(src);
+    dev_free(dst);
+    if (e || es) return e ? e : es;
+    *value_out = (which == HCNN_CEIL_COPY ? 2.0 : 1.0) * (double)bytes / (ms * 1e-3) / 1e9;
+    return HCNN_OK;
+  }
+  void* out = nullptr;
+  if ((e = dev_malloc(&out, kRateThreads * 4))) return e;
+  RateArgs a;
+  a.out = (uint32_t*)out; a.seed = 12345u;
+  const size_t grid = (size_t)c->compute_units * 8;          // 8 workgroups of 256 per compute unit: full occupancy
+  switch (which) {
+    case HCNN_CEIL_MUL_LO: e = timed_launches<RateKernel<kRateMulLo>>(c, grid, a, 5, &ms); break;
+    case HCNN_CEIL_MUL_HI: e = timed_launches<RateKernel<kRateMulHi>>(c, grid, a, 5, &ms); break;
+    case HCNN_CEIL_MAD_U64: e = timed_launches<RateKernel<kRateMadU64>>(c, grid, a, 5, &ms); break;
+    case HCNN_CEIL_MAD_I64: e = timed_launches<RateKernel<kRateMadI64>>(c, grid, a, 5, &ms); break;
+    default: e = timed_launches<RateKernel<kRateAdd>>(c, grid, a, 5, &ms); break;
+  }
+  dev_free(out);
+  if (e) return e;
+  *value_out = (double)grid * kRateThreads * kRateIters * kRateChains / (ms * 1e-3) / 1e12;
   return HCNN_OK;
 }
 

@@ -107,6 +107,16 @@ inline size_t max_lds_bytes() { return 160 * 1024; }
 inline uint32_t compute_unit_count() { return 1; }   // small rounds: the checker's little batches reach every batch-splitting path
 HCNN_HD void atomic_inc64(unsigned long long* p) { *p += 1; }
 HCNN_HD void atomic_max32(uint32_t* p, uint32_t v) { if (v > *p) *p = v; }
+// Workgroups of kernel K that one compute unit holds at a time.  The checker has no device to ask: it counts 16
+// wavefronts per compute unit (8 for workgroups of 256 threads, the shape whose register use halves the occupancy
+// on the device), which with its single compute unit gives rounds of a few workgroups.
+template <class K, class Args>
+int resident_workgroups_per_cu(size_t, int* out) {
+  const int waves = K::kThreads / 64 > 0 ? K::kThreads / 64 : 1;
+  *out = (K::kThreads == 256 ? 8 : 16) / waves;
+  if (*out < 1) *out = 1;
+  return 0;
+}
 
 template <class K, int PH, int END>
 struct EmuPhases {
@@ -218,6 +228,22 @@ int launch(hcnn_stream_t s, size_t grid, size_t lds_bytes, const Args& a) {
   }
   hipLaunchKernelGGL((kernel_entry<K, Args>), dim3((unsigned)grid), dim3(K::kThreads), lds_bytes, s, a);
   return (int)hipGetLastError();
+}
+
+// Workgroups of kernel K (with lds_bytes of dynamic LDS each) that one compute unit holds at a time, as the runtime
+// derives it from the compiled kernel's register and LDS use.
+template <class K, class Args>
+int resident_workgroups_per_cu(size_t lds_bytes, int* out) {
+  if (lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_entry<K, Args>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return (int)e;
+  }
+  int n = 0;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_entry<K, Args>, K::kThreads, lds_bytes);
+  if (e != hipSuccess) return (int)e;
+  *out = n > 0 ? n : 1;
+  return 0;
 }
 #endif
 

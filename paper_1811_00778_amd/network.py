@@ -147,14 +147,8 @@ def _main(argv=None):
     ap.add_argument("--k", type=int, default=0, help="30-bit primes in q (default: 11 for mnist, 10 for cifar10)")
     ap.add_argument("--t", type=int, default=0, help="plaintext modulus (default: 65537 / 2424833)")
     ap.add_argument("--reps", type=int, default=2)
-    ap.add_argument("--first-layers", type=int, default=0, help="evaluate only the first N layers")
-    ap.add_argument("--filters", type=int, default=0, help="override the filter count of the first layer")
     args = ap.parse_args(argv)
     spec, in_shape = (MNIST_HCNN, MNIST_INPUT) if args.name == "mnist" else (CIFAR10_HCNN, CIFAR10_INPUT)
-    if args.first_layers:
-        spec = spec[:args.first_layers]
-    if args.filters:
-        spec = (("conv", args.filters) + tuple(spec[0][2:]),) + tuple(spec[1:])
     k = args.k or (11 if args.name == "mnist" else 10)
     t = args.t or (65537 if args.name == "mnist" else 2424833)
     q, p = binding.choose_moduli(args.n, k, t)

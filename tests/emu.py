@@ -18,7 +18,13 @@ from paper_1811_00778_amd._ops import OpsMixin
 _ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 _SRC_DIR = os.path.join(_ROOT, "paper_1811_00778_amd", "csrc")
 _OUT_DIR = os.path.join(_ROOT, "tests", "_build")
-_OUT = os.path.join(_OUT_DIR, "libhcnn_emu.so")
+# HCNN_EMU_SANITIZE=1: build and load the checker with AddressSanitizer and UndefinedBehaviorSanitizer (host code
+# only: this is the one build in which the kernels' indexing runs under a bounds checker).  The sanitizer runtime
+# has to be in the process before Python starts, so run it as
+#     HCNN_EMU_SANITIZE=1 LD_PRELOAD=$(g++ -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+#         python -m pytest tests/test_emu_parity.py -q
+SANITIZE = os.environ.get("HCNN_EMU_SANITIZE", "") not in ("", "0")
+_OUT = os.path.join(_OUT_DIR, "libhcnn_emu_san.so" if SANITIZE else "libhcnn_emu.so")
 _lib = None
 
 
@@ -28,7 +34,9 @@ def build() -> str:
     if os.path.exists(_OUT) and all(os.path.getmtime(s) <= os.path.getmtime(_OUT) for s in srcs):
         return _OUT
     tmp = _OUT + ".tmp.%d" % os.getpid()
-    subprocess.check_call(["g++", "-std=c++17", "-O2", "-DHCNN_HOSTEMU", "-fPIC", "-shared", "-Wall", "-Wextra",
+    extra = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+        if SANITIZE else ["-O2"]
+    subprocess.check_call(["g++", "-std=c++17"] + extra + ["-DHCNN_HOSTEMU", "-fPIC", "-shared", "-Wall", "-Wextra",
                            "-Wno-unused-parameter", "-Wno-unknown-pragmas", "-o", tmp,
                            os.path.join(_SRC_DIR, "hcnn.cpp")])
     os.replace(tmp, _OUT)

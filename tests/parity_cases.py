@@ -221,6 +221,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
             s.ctx.set_fusion(mode)
             out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
             assert np.array_equal(out, want), ("square_relin, relinearisation form", mode, n, k)
+        s.ctx.set_fusion(0)
     s.ctx.close()
 
 

@@ -57,22 +57,33 @@ def test_square_relin_chunked_ragged(backend):
 
 
 def test_square_relin_batch_split_into_rounds_and_remainder(backend):
-    """This build counts one compute unit (16 waves: at n = 1024, two primes, a round of the one-kernel relinearisation is
-    8 ciphertexts and six rounds of the one-kernel tensor are 96 (ciphertext, limb) pairs), so a batch of 26 takes the
-    default policy's mixed route: the tensor in one kernel, 24 ciphertexts through the one-kernel relinearisation, 2
-    through the separate kernels."""
+    """The default policy sizes its rounds from the occupancy that the platform layer reports for the compiled
+    kernels (this build: a fixed count for its single compute unit).  A batch of three rounds of the one-kernel
+    relinearisation plus two ciphertexts, large enough for the one-kernel tensor, must take the mixed route: the
+    tensor in one kernel, the whole rounds through the one-kernel relinearisation, the two left over through the
+    separate kernels."""
     s = pc.Setup(backend, 1024, 2)
     s.ctx.set_relin_key(backend.dev(s.evk))
-    n_ct, L = 26, 2 + len(s.p)
+    rnd, L = s.ctx.relin_fused_round(), 2 + len(s.p)
+    assert rnd >= 1
+    n_ct = 3 * rnd + 2
+    assert n_ct * L >= s.ctx.tensor_fused_threshold()
     cts = pc.gen.uniform_residues(s.rng, s.q, 1024, lead=(n_ct, 2))
     s.ctx.set_profile(True)
     out = backend.host(s.ctx.ct_square_relin(backend.dev(cts)))
     prof = s.ctx.profile()
     assert prof["tensor"][0] == 1 and prof["tensor"][1] == n_ct * L * 5
-    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 24 * 2 * (2 + 2)
+    assert prof["relin_fused"][0] == 1 and prof["relin_fused"][1] == 3 * rnd * 2 * (2 + 2)
     assert prof["relin_mac"][0] == 1 and prof["ntt_fwd"][1] == 2 * 2 * 2            # the two left over: digit rows only
-    for i in (0, 23, 24, 25):
+    for i in (0, 3 * rnd - 1, 3 * rnd, 3 * rnd + 1):
         assert np.array_equal(out[i], pc.fv.square_relin(s.octx, cts[i], s.evk)), i
+    # a batch below the tensor threshold and below 3/4 of a round: separate kernels throughout
+    s.ctx.reset_stats()
+    small = max(1, (3 * rnd - 1) // 4)
+    s.ctx.ct_square_relin(backend.dev(cts[:small]))
+    prof = s.ctx.profile()
+    if small * L < s.ctx.tensor_fused_threshold() and small * 4 < rnd * 3:
+        assert prof["tensor"][0] == 0 and prof["relin_fused"][0] == 0 and prof["relin_mac"][0] >= 1
     s.ctx.close()
 
 
@@ -162,3 +173,47 @@ def test_plaintext_crt_channels(backend):
 
 def test_small_network_layer_by_layer(backend):
     pc.check_small_network(backend)
+
+
+def test_wrappers_check_every_shape_before_the_call(backend):
+    """The C ABI takes bare pointers, so the Python wrappers are the only place where a wrongly sized buffer can be
+    caught before a kernel reads or writes past it: each argument's full shape is checked, and a scalar MAC whose
+    output overlaps its input is refused."""
+    n, k = 1024, 2
+    s = pc.Setup(backend, n, k)
+    ctx, dev = s.ctx, backend.dev
+    kr = s.kr
+    good = dict(s=dev(kr["s"]), a=dev(kr["a"]), e=dev(kr["e"]), a_evk=dev(kr["a_evk"]), e_evk=dev(kr["e_evk"]))
+    ctx.keygen(**good)
+    for name, bad in (("s", np.zeros(n // 2, np.int32)), ("a", np.zeros((k + 1, n), np.uint32)),
+                      ("e", np.zeros((2, n), np.int32)), ("a_evk", np.zeros((k, k, n // 2), np.uint32)),
+                      ("e_evk", np.zeros((k + 1, n), np.int32))):
+        with pytest.raises(ValueError):
+            ctx.keygen(**dict(good, **{name: dev(bad)}))
+    with pytest.raises(ValueError):
+        ctx.keygen(good["s"], good["a"], good["e"], good["a_evk"], None)
+    slots, polys, er, cts = s.encrypt_oracle(2)
+    pk, m, u, e1, e2 = dev(s.pk), dev(polys), dev(er["u"]), dev(er["e1"]), dev(er["e2"])
+    ctx.encrypt(pk, m, u, e1, e2)
+    with pytest.raises(ValueError):
+        ctx.encrypt(dev(np.zeros((2, k, n // 2), np.uint32)), m, u, e1, e2)
+    with pytest.raises(ValueError):
+        ctx.encrypt(pk, m, dev(er["u"][:1]), e1, e2)
+    with pytest.raises(ValueError):
+        ctx.encrypt(pk, m, u, e1, dev(np.zeros((2, n + 4), np.int32)))
+    dcts = dev(cts)
+    with pytest.raises(ValueError):
+        ctx.decrypt(dev(np.zeros(n + 1, np.int32)), dcts)
+    with pytest.raises(ValueError):
+        ctx.noise_bits(dev(np.zeros((1, n), np.int32)), dcts)
+    ctx.set_relin_key(dev(s.evk))
+    with pytest.raises(ValueError):
+        ctx.ct_mul_relin(dcts, dcts, out=dev(np.zeros((1, 2, k, n), np.uint32)))
+    with pytest.raises(ValueError):
+        ctx.ct_square_relin(dcts, out=dev(np.zeros((3, 2, k, n), np.uint32)))
+    idx, w = dev(np.array([[0, 1]], np.uint32)), dev(np.ones((1, 1, 2), np.int32))
+    with pytest.raises(ValueError):
+        ctx.ct_scalar_mac(dcts, idx, w, 1, out=dcts[:1].reshape((1, 1, 2, k, n)))        # overlaps its input
+    with pytest.raises(ValueError):
+        ctx.ct_scalar_mac(dcts, idx, dev(np.ones((1, 1, 3), np.int32)), 1)
+    ctx.close()
