@@ -548,8 +548,8 @@ struct MacKernelDirect {
 
 // Main variant: the gather row and the F*T weights of the group are staged in LDS once per
 // workgroup (validated while staging: a bad index or weight becomes a zero-weight term on input 0;
-// the row is padded with such terms to a multiple of kMacBatch), so the term loop reads them with
-// broadcast LDS reads and carries no data-dependent branches.  Inputs are fetched kMacBatch terms
+// the row is padded to a multiple of kMacBatch with fetches of its last input that enter no sum), so the
+// term loop reads them with broadcast LDS reads and carries no data-dependent branches.  Inputs are fetched kMacBatch terms
 // ahead of their use (double buffering in registers) to keep HBM requests in flight during the
 // multiply-adds.  Requires chunk % kMacBatch == 0.
 constexpr uint32_t kMacBatch = 4;
@@ -581,18 +581,17 @@ struct MacKernel {
       const uint32_t* idx = a.idx + (size_t)g * a.T;
       const int32_t* w = a.w + (size_t)g * a.F * a.T;
       for (uint32_t tau = tid; tau < Tpad + 2 * kMacBatch; tau += kThreads) {
-        if (tau >= Tpad) {                 // read-ahead slots of the last batches
-          l_idx[tau] = 0;
-          continue;
-        }
+        // the padding terms and the read-ahead slots of the last batches fetch the row's last input once more
+        // (the compute unit's cache has just seen it); they take part in no sum
         const bool pad = tau >= a.T;
-        uint32_t src = pad ? 0u : idx[tau];
+        uint32_t src = idx[pad ? a.T - 1 : tau];
         const bool bad_src = src >= a.n_in;
         if (bad_src) {
           src = 0;
-          if (tile == 0) atomic_inc64(a.bad_counter);
+          if (tile == 0 && !pad) atomic_inc64(a.bad_counter);
         }
         l_idx[tau] = src * (ct_words32 / 4);   // offset of the input in 16-byte units (the host checked that it fits)
+        if (tau >= Tpad) continue;
 #pragma unroll
         for (int f = 0; f < FT; ++f) {
           int32_t wf = pad ? 0 : w[(size_t)f * a.T + tau];
@@ -622,6 +621,7 @@ struct MacKernel {
       auto consume = [&](const U4 (&buf)[kMacBatch], uint32_t t) {
 #pragma unroll
         for (uint32_t b = 0; b < kMacBatch; ++b) {
+          if (t + b >= a.T) break;              // padding terms of the last batch (uniform over the workgroup)
 #pragma unroll
           for (int f = 0; f < FT; ++f) {
             const int64_t wf = l_w[(size_t)f * Tpad + t + b];
@@ -640,7 +640,7 @@ struct MacKernel {
       };
       // two register buffers used alternately: the loads of the next batch are in flight while the
       // current one is consumed.  Every fetch is unconditional (the gather row is followed by 2*kMacBatch
-      // entries that point at input 0) so that the number of loads in flight is the same on every path
+      // entries that name its last input again) so that the number of loads in flight is the same on every path
       // and the compiler can wait for exactly the older batch.
       U4 buf_a[kMacBatch], buf_b[kMacBatch];
       fetch(buf_a, 0);
