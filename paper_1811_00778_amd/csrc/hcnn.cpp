@@ -325,7 +325,7 @@ int upload(hcnn_ctx* c, const std::vector<T>& h, T** d) {
 }
 
 template <class K> struct KernelClass { static constexpr int id = HCNN_PROF_OTHER; };
-template <int A, int B, int C> struct KernelClass<NttFwd<A, B, C>> { static constexpr int id = HCNN_PROF_NTT_FWD; };
+template <int A, int B, int C, int D> struct KernelClass<NttFwd<A, B, C, D>> { static constexpr int id = HCNN_PROF_NTT_FWD; };
 template <int A, int B, int C> struct KernelClass<NttInv<A, B, C>> { static constexpr int id = HCNN_PROF_NTT_INV; };
 template <> struct KernelClass<ExtKernel> { static constexpr int id = HCNN_PROF_BASE_EXT; };
 template <int A, int B> struct KernelClass<ExtKernelT<A, B>> { static constexpr int id = HCNN_PROF_BASE_EXT; };
@@ -592,6 +592,24 @@ int ntt_launch(hcnn_ctx* c, const NttRows& r, bool inverse, int io) {
     if (io == kNttLoadTensorMul) return run<NttInv<LOGN, LOGR, kNttLoadTensorMul>>(c, g3, lds, a, r.rows);
     if (io == kNttStoreAdd) return run<NttInv<LOGN, LOGR, kNttStoreAdd>>(c, r.rows, lds, a);
     return run<NttInv<LOGN, LOGR>>(c, r.rows, lds, a);
+  }
+  // The largest ring runs its forward transforms as two workgroups per row (first stage folded into the load):
+  // a whole row of it takes the LDS of a compute unit, half a row leaves room for two workgroups.  Each of the two
+  // reads the whole row, so the form needs an output that is not its input.
+  if constexpr (LOGN == 15) {
+    if (r.in != r.out) {
+      const size_t lds_h = NttGeom<LOGN - 1, LOGR>::kLdsBytes;
+      if (io == kNttLoadDigit) {
+        using K = NttFwd<LOGN, LOGR, kNttLoadDigit, 1>;
+        return run<K>(c, K::grid(ntt_grouped_grid(r.rows, r.cycle)), lds_h, a, r.rows);
+      }
+      if (io == kNttStoreLazy) {
+        using K = NttFwd<LOGN, LOGR, kNttStoreLazy, 1>;
+        return run<K>(c, K::grid(r.rows), lds_h, a, r.rows);
+      }
+      using K = NttFwd<LOGN, LOGR, kNttPlain, 1>;
+      return run<K>(c, K::grid(r.rows), lds_h, a, r.rows);
+    }
   }
   if (io == kNttLoadDigit)
     return run<NttFwd<LOGN, LOGR, kNttLoadDigit>>(c, ntt_grouped_grid(r.rows, r.cycle), lds, a, r.rows);
@@ -995,8 +1013,11 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
     uint32_t* const b_acc = acc + s0 * 2 * k * rn;
     // 1. centred lift of c0, c1 extended to the auxiliary primes (only the new rows are written);
     // 2. forward NTT over all k + k' limbs, the first k read from the ciphertext itself
+    // (n = 32768: the new rows are staged in the array of the tensor, free until step 3, because the two-workgroup
+    // transform of that ring cannot work in place)
+    uint32_t* const b_new = c->logn == 15 ? b_d : b_ext;
     ExtArgs ea;
-    ea.in = in + c0 * ct_words; ea.out = b_ext; ea.bc = c->ext; ea.n = n; ea.band = c->band;
+    ea.in = in + c0 * ct_words; ea.out = b_new; ea.bc = c->ext; ea.n = n; ea.band = c->band;
     ea.fallback_counter = c->d_counters;
     if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
     const bool tensor_fused = takes_tensor_fused(cc);
@@ -1014,13 +1035,14 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
         default: e = HCNN_ERR_N; break;
       }
       if (e) return e;
-    } else if ((e = ntt_dense(c, b_ext, b_ext, cc * 2 * L, L, false, kNttStoreLazy, in + c0 * ct_words, k))) {
+    } else if ((e = ntt_dense(c, b_new, b_ext, cc * 2 * L, L, false, kNttStoreLazy, in + c0 * ct_words, k))) {
       return e;
     }
     if (in_b) {
-      ea.in = in_b + c0 * ct_words; ea.out = b_ext_b;
+      uint32_t* const b_new_b = c->logn == 15 ? b_d : b_ext_b;
+      ea.in = in_b + c0 * ct_words; ea.out = b_new_b;
       if ((e = ext_dispatch(c, cc * 2 * bpp, ea))) return e;
-      if ((e = ntt_dense(c, b_ext_b, b_ext_b, cc * 2 * L, L, false, kNttStoreLazy, in_b + c0 * ct_words, k))) return e;
+      if ((e = ntt_dense(c, b_new_b, b_ext_b, cc * 2 * L, L, false, kNttStoreLazy, in_b + c0 * ct_words, k))) return e;
     }
     // 3+4. tensor formed while loading, then back to coefficients: the integer tensor, known mod q*p
     if (in_b) {

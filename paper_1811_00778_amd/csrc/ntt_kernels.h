@@ -137,26 +137,44 @@ struct NttGeom {
 };
 
 // ------------------------------------------------------------------------- forward
-template <int LOGN, int LOGR, int IO = kNttPlain>
+// SPLIT = 1: two workgroups per row.  The first stage of the forward transform pairs element i with element
+// i + n/2 and leaves two halves that never meet again; workgroup (row, half) computes its half of that stage while
+// loading (it reads both halves of the row, the second reader out of L2) and then runs the remaining log2(n) - 1
+// stages on n/2 residues.  Half the LDS and half the threads per workgroup: for the largest ring, whose whole row
+// fills the LDS of a compute unit, two workgroups fit where one did, and they are out of step with each other.
+template <int LOGN, int LOGR, int IO = kNttPlain, int SPLIT = 0>
 struct NttFwd {
   static constexpr bool kFused = IO == kNttFusedMac || IO == kNttFusedMac16 || IO == kNttFusedMacAny;
   static constexpr bool kToRegs = IO == kNttToRegs0 || IO == kNttToRegs1;
   static_assert(IO == kNttPlain || IO == kNttLoadDigit || IO == kNttStoreLazy || kFused || kToRegs,
                 "forward NTT: plain, digit load, lazy store, fused inner product or register output");
-  using G = NttGeom<LOGN, LOGR>;
+  static_assert(SPLIT == 0 || (SPLIT == 1 && !kFused && !kToRegs), "the split form stores its rows");
+  using G = NttGeom<LOGN - SPLIT, LOGR>;      // the stages after the split one
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
   static constexpr bool kDigitIn = IO == kNttLoadDigit || kFused;
   using Regs = std::conditional_t<kFused, RelinRegs<G::R>, std::conditional_t<kToRegs, TensorRegs<G::R>, NoRegs>>;
+  // workgroups of a launch over `slots` row positions (a multiple of the die count for the split form)
+  static size_t grid(size_t slots) { return SPLIT ? 2 * ((slots + kNttXcds - 1) / kNttXcds * kNttXcds) : slots; }
 
   template <int PH>
   HCNN_HD static void phase(const NttArgs& a, unsigned bid, int tid, uint32_t* lds, Regs& regs) {
-    constexpr int N = G::N, R = G::R;
+    constexpr int N = 1 << LOGN, R = G::R;                 // N: residues of a row in memory
+    constexpr int LOGM = LOGN - SPLIT;                     // stages S0 .. of this workgroup run on 2^LOGM residues
     constexpr int S0 = G::s0(PH), NS = G::ns(PH), NET = 1 << NS, C = R / NET;
-    constexpr int LOG_TLAST = LOGN - S0 - NS, TLAST = 1 << LOG_TLAST;
+    constexpr int LOG_TLAST = LOGM - S0 - NS, TLAST = 1 << LOG_TLAST;
     constexpr bool kFirst = PH == 0, kLast = PH == kPhases - 1;
     if constexpr (kFused || kToRegs) tid = opaque(tid);
 
+    uint32_t half = 0;
+    if constexpr (SPLIT) {
+      // both halves of a row on one die, next to each other in time
+      half = (bid / kNttXcds) & 1u;
+      bid = (bid / (2 * kNttXcds)) * kNttXcds + bid % kNttXcds;
+      if constexpr (!kDigitIn) {
+        if (bid >= a.n_rows) return;                       // padding workgroups of the last round
+      }
+    }
     if constexpr (kDigitIn) {
       bid = ntt_grouped_index(bid, a.limb_cycle);      // the k transforms of one digit row share a die
       if (bid >= a.n_rows) return;
@@ -193,7 +211,21 @@ struct NttFwd {
           gin = a.aux + ((size_t)(bid / a.limb_cycle) * a.own_limbs + bid % a.limb_cycle) * N;
       }
     }
-    if constexpr (!kFused && !kToRegs) gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N;
+    if constexpr (!kFused && !kToRegs)
+      gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N + (size_t)half * (N / 2);
+    // split form: the butterfly of the first stage (node 1) on the way in -- this half's output of the pair
+    // (i, i + n/2).  X is brought below 2p first (rows may arrive lazily reduced below 4p), the product lies in
+    // [0, 2p): X + T and X - T + 2p are valid inputs of the stages that follow.
+    [[maybe_unused]] const ShoupConst w_split = SPLIT ? ldc(tw, 1) : ShoupConst{0, 0};
+    auto load_first = [&](uint32_t idx) -> uint32_t {
+      if constexpr (SPLIT) {
+        const uint32_t X = csub(gin[idx], two_p);
+        const uint32_t T = shoup_lazy(gin[idx + N / 2], w_split.w, w_split.ws, p);
+        return half ? X + two_p - T : X + T;
+      } else {
+        return gin[idx];
+      }
+    };
 
 #pragma unroll
     for (int c = 0; c < C; ++c) {
@@ -204,10 +236,11 @@ struct NttFwd {
       uint32_t v[NET];
 #pragma unroll
       for (int e = 0; e < NET; ++e)
-        v[e] = kFirst ? gin[base + (uint32_t)e * TLAST] : lds[lds_elem<LOG_TLAST>(sbase, e)];
+        v[e] = kFirst ? load_first(base + (uint32_t)e * TLAST) : lds[lds_elem<LOG_TLAST>(sbase, e)];
       // (kNttLoadDigit: a digit lies in [0, q_i) and every prime in (2^29, 2^30), so it is below 2p for this
       // row's prime p: a valid lazily reduced input of the butterflies as it stands)
-      const uint32_t root = (1u << S0) + i;
+      // node of the twiddle tree over the whole row: the half's own sub-tree in the split form
+      const uint32_t root = SPLIT ? ((2u + half) << S0) + i : (1u << S0) + i;
 #pragma unroll
       for (int l = 0; l < NS; ++l) {
         const int half = NET >> (l + 1);

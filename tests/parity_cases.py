@@ -225,7 +225,7 @@ def check_square_relin(backend, n, k, n_random=2, n_genuine=1, seed_id=1, chunk=
     s.ctx.close()
 
 
-def check_mul_relin(backend, n, k, seed_id=1, force_exact=False):
+def check_mul_relin(backend, n, k, seed_id=1, force_exact=False, check_decrypt=True):
     """General HMult on genuine and on uniformly random ciphertext pairs."""
     s = Setup(backend, n, k, seed_id=seed_id, stream=3)
     s.ctx.set_relin_key(backend.dev(s.evk))
@@ -239,8 +239,9 @@ def check_mul_relin(backend, n, k, seed_id=1, force_exact=False):
     want = np.stack([fv.hmult(s.octx, a[i], b[i], s.evk) for i in range(len(a))])
     assert np.array_equal(out, want), ("mul_relin", n, k)
     assert np.array_equal(out[3], fv.square_relin(s.octx, a[3], s.evk))
-    m = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[0]), n, s.t)
-    assert np.array_equal(m, (slots[0].astype(np.uint64) * slots[1] % s.t).astype(np.uint32))
+    if check_decrypt:
+        m = fv.slot_decode(fv.decrypt(s.octx, s.kr["s"], out[0]), n, s.t)
+        assert np.array_equal(m, (slots[0].astype(np.uint64) * slots[1] % s.t).astype(np.uint32))
     # in place on the first operand, relinearisation forced into its one-kernel form
     s.ctx.set_fusion(2)
     buf = backend.dev(a)

@@ -138,6 +138,12 @@ def test_square_relin_at_a_degree_with_die_aware_block_orders(backend):
     pc.check_square_relin(backend, 8192, 2, n_random=6, n_genuine=0, relin_order=2)    # key-major order forced
 
 
+def test_square_relin_largest_ring_two_workgroups_per_forward_row(backend):
+    # n = 32768: the forward transforms run as two workgroups per row, out of place, the extended rows staged in the
+    # array of the tensor
+    pc.check_square_relin(backend, 32768, 2, n_random=2, n_genuine=0)
+
+
 def test_general_hmult(backend):
     pc.check_mul_relin(backend, 1024, 2)
     pc.check_mul_relin(backend, 2048, 3, force_exact=True)

@@ -143,6 +143,7 @@ def test_general_hmult(backend):
     pc.check_mul_relin(backend, 1024, 2)
     pc.check_mul_relin(backend, 2048, 3, force_exact=True)
     pc.check_mul_relin(backend, 1024, 8)
+    pc.check_mul_relin(backend, 32768, 2, check_decrypt=False)     # a 60-bit q has no room for the product's noise
 
 
 def test_conv_square_layer(backend):
