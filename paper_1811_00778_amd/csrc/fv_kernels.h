@@ -108,12 +108,12 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
   uint32_t S = 0;
   for (uint32_t i = 0; i < bc.ks; ++i) {
     const Mod m = ldc(bc.src_mod, i);
-    const uint32_t z = shoup_mul(in(i), ldc(bc.zmul, i), m.p);
+    const uint32_t z = shoup_mul(in(i), ldc(bc.zmul, i), m);
     zcol[i * stride] = z;
     S += frac_est(z, m);
   }
   auto exact = [&]() {
-    for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), ldc(bc.xmul, i), ldc(bc.src_mod, i).p);
+    for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), ldc(bc.xmul, i), ldc(bc.src_mod, i));
     return garner_gt_half(bc, gcol, stride);
   };
   return bconv_round(S, band, exact, fallback_counter);
@@ -192,13 +192,13 @@ struct ExtKernelT {
 #pragma unroll
     for (int i = 0; i < K; ++i) {
       const Mod m = ldc(a.bc.src_mod, i);
-      z[i] = shoup_mul(x[i], ldc(a.bc.zmul, i), m.p);
+      z[i] = shoup_mul(x[i], ldc(a.bc.zmul, i), m);
       S += frac_est(z[i], m);
     }
     auto exact = [&]() {
       uint32_t* col = lds + tid;
 #pragma unroll
-      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(x[i], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i).p);
+      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(x[i], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i));
       return garner_gt_half(a.bc, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact, a.fallback_counter);
@@ -306,13 +306,13 @@ struct ScaleKernelR {
 #pragma unroll
       for (int i = 0; i < K; ++i) {
         const Mod m = ldc(a.to_p.src_mod, i);
-        z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m.p);
+        z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m);
         S += frac_est(z[i], m);
       }
     }
     auto exact_q = [&]() {
       for (uint32_t i = 0; i < (uint32_t)K; ++i)
-        col[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i).p);
+        col[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i));
       return garner_gt_half(a.to_p, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact_q, a.fallback_counter);
@@ -350,7 +350,7 @@ struct ScaleKernelR {
       }
       col[j * kThreads] = yj;                                     // made canonical by the exact path if it runs
       const Mod sm = ldc(a.to_q.src_mod, j);
-      const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm.p);
+      const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm);
       S2 += frac_est(z2, sm);
       const uint32_t* b2 = a.to_q.Bp + (size_t)j * K;
 #pragma unroll
@@ -746,8 +746,8 @@ struct AddSmallKernel {
     const Mod m = ldc(a.mods, l);
     const uint32_t sv = small_to_res(a.small[poly * a.n + c], m);
     uint32_t r = a.subtract_small ? sub_mod(a.x[row * a.n + c], sv, m.p) : add_mod(a.x[row * a.n + c], sv, m.p);
-    if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
-    if (a.msg64) r = add_mod(r, shoup_mul(reduce64(a.msg64[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
+    if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), ldc(a.scale, l), m), m.p);
+    if (a.msg64) r = add_mod(r, shoup_mul(reduce64(a.msg64[poly * a.n + c], m), ldc(a.scale, l), m), m.p);
     a.out[(poly * a.out_poly_rows + a.out_row0 + l) * a.n + c] = r;
   }
 };
@@ -971,7 +971,7 @@ struct NoiseKernel {
     uint32_t* dig = lds + tid;                                   // mixed-radix digits
     uint32_t* word = lds + (size_t)ks * kThreads + tid;          // multiword |r|, least significant first
     for (uint32_t i = 0; i < ks; ++i)
-      dig[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i).p);
+      dig[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i));
     if (garner_gt_half(a.bc, dig, kThreads)) {
       // digits of q - R: zero while the lower digits of R are zero, q_i - d_i at the first non-zero digit,
       // q_i - 1 - d_i above it

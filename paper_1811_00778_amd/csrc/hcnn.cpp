@@ -127,6 +127,8 @@ Mod h_mod(uint32_t p) {
   m.c32 = (uint32_t)((1ull << 32) % p);
   m.c32s = (uint32_t)(((uint64_t)m.c32 << 32) / p);
   m.mu = (uint32_t)((1ull << 61) / p);
+  m.pn = 0u - p;
+  m.pad[0] = m.pad[1] = m.pad[2] = 0;
   return m;
 }
 
@@ -476,6 +478,8 @@ int build_tables(hcnn_ctx* c) {
     for (uint32_t node = 1; node < n; ++node) {
       const uint32_t e = h_brev(node, (int)c->logn);
       twf[(size_t)l * n + node] = h_shoup(pw[e], p);
+      // the forward butterflies use the twiddle negated modulo 2^32 (their product is kept negated)
+      twf[(size_t)l * n + node].w = 0u - twf[(size_t)l * n + node].w;
       twi[(size_t)l * n + node] = h_shoup(pw[2 * n - e], p);
     }
     NttLimb nl;
@@ -487,7 +491,8 @@ int build_tables(hcnn_ctx* c) {
     nl.ninv_r = h_shoup(ninv_r, p);
     nl.w1ninv_r = h_shoup(h_mulmod(twi[(size_t)l * n + 1].w, ninv_r, p), p);
     nl.pinv = h_neg_inv32(p);
-    nl.pad[0] = nl.pad[1] = nl.pad[2] = 0;
+    nl.zero = 0;
+    nl.pad[0] = nl.pad[1] = 0;
     mods.push_back(nl.m);
     limbs.push_back(nl);
   }

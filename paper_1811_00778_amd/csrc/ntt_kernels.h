@@ -29,7 +29,8 @@ struct NttLimb {
   ShoupConst ninv_r;    // n^-1 * 2^32 mod p
   ShoupConst w1ninv_r;  // (inverse twiddle of node 1) * n^-1 * 2^32 mod p
   uint32_t pinv;        // -p^-1 mod 2^32
-  uint32_t pad[3];
+  uint32_t zero;        // 0, unknown to the compiler: zero - w is the negated twiddle and stays one (see the inverse butterfly)
+  uint32_t pad[2];
 };
 
 // Row r (= workgroup index) belongs to group r / limb_cycle and limb limb_base + r % limb_cycle.
@@ -83,7 +84,7 @@ struct NttArgs {
   const uint32_t* in;
   uint32_t* out;            // may equal `in`
   const uint32_t* aux;      // kNttStoreAdd: the addend; kNttLoadTensorMul: the second operand
-  const ShoupConst* tw;     // [L][n] node table (forward or inverse)
+  const ShoupConst* tw;     // [L][n] node table (forward: {-w mod 2^32, w'}; inverse: {w, w'})
   const NttLimb* limbs;     // [L]
   uint32_t limb_cycle;
   uint32_t limb_base;
@@ -214,14 +215,14 @@ struct NttFwd {
     if constexpr (!kFused && !kToRegs)
       gout = a.out + ntt_row(bid, a.limb_cycle, a.out_group_rows, a.out_row0) * N + (size_t)half * (N / 2);
     // split form: the butterfly of the first stage (node 1) on the way in -- this half's output of the pair
-    // (i, i + n/2).  X is brought below 2p first (rows may arrive lazily reduced below 4p), the product lies in
+    // (i, i + n/2).  X is brought below 2p first (rows may arrive lazily reduced below 4p), the product T lies in
     // [0, 2p): X + T and X - T + 2p are valid inputs of the stages that follow.
     [[maybe_unused]] const ShoupConst w_split = SPLIT ? ldc(tw, 1) : ShoupConst{0, 0};
     auto load_first = [&](uint32_t idx) -> uint32_t {
       if constexpr (SPLIT) {
-        const uint32_t X = csub(gin[idx], two_p);
-        const uint32_t T = shoup_lazy(gin[idx + N / 2], w_split.w, w_split.ws, p);
-        return half ? X + two_p - T : X + T;
+        const uint32_t X = csub(gin[idx], two_p), Y = gin[idx + N / 2];
+        const uint32_t negT = mulhi32(Y, w_split.ws) * p + Y * w_split.w;
+        return half ? X + two_p + negT : X - negT;
       } else {
         return gin[idx];
       }
@@ -251,7 +252,8 @@ struct NttFwd {
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
             const uint32_t X = csub(v[ia], two_p);                          // [0, 2p)
-            const uint32_t negT = mulhi32(v[ib], w.ws) * p - v[ib] * w.w;   // -(y*w mod p) - {0,p}  (mod 2^32)
+            // the forward table holds -w (mod 2^32): q*p - y*w is then a multiplication and a multiply-add
+            const uint32_t negT = mulhi32(v[ib], w.ws) * p + v[ib] * w.w;   // -(y*w mod p) - {0,p}  (mod 2^32)
             v[ia] = X - negT;                                              // X + T        in [0, 4p)
             v[ib] = X + two_p + negT;                                      // X - T + 2p   in (0, 4p)
           }
@@ -475,6 +477,7 @@ struct NttInv {
         }
       }
       const uint32_t root = (1u << S0) + i;
+      const uint32_t pn = L.m.pn;
 #pragma unroll
       for (int l = NS - 1; l >= 0; --l) {
         const int half = NET >> (l + 1);
@@ -484,6 +487,10 @@ struct NttInv {
           constexpr bool kMont = IO == kNttLoadTensor || IO == kNttLoadTensorMul || kTensorRegs;
           const ShoupConst w = top ? (kMont ? L.w1ninv_r : L.w1ninv) : ldc(tw, (root << l) + h);
           const ShoupConst nv = kMont ? L.ninv_r : L.ninv;
+          // Both forms of the lazy product are a multiplication and a multiply-add: x*w + q*(-p), and negated
+          // x*(-w) + q*p.  -p and the zero that -w is taken from come out of the table, so that the compiler
+          // keeps the sums (it would turn a visible negation back into two multiplications and a subtraction).
+          const uint32_t wn = L.zero - w.w;
 #pragma unroll
           for (int x = 0; x < half; ++x) {
             const int ia = h * 2 * half + x, ib = ia + half;
@@ -494,9 +501,9 @@ struct NttInv {
             const uint32_t X = v[ia], Y = v[ib];
             const uint32_t S = y_neg ? X - Y : X + Y;                   // [0, 4p)
             const uint32_t D = y_neg ? X + two_p + Y : X + two_p - Y;   // (0, 4p)
-            v[ia] = top ? shoup_lazy(S, nv.w, nv.ws, p) : csub(S, two_p);
-            v[ib] = out_neg ? mulhi32(D, w.ws) * p - D * w.w            // -(D * w mod p) - {0, p}  (mod 2^32)
-                            : shoup_lazy(D, w.w, w.ws, p);              // [0, 2p)
+            v[ia] = top ? S * nv.w + mulhi32(S, nv.ws) * pn : csub(S, two_p);
+            v[ib] = out_neg ? D * wn + mulhi32(D, w.ws) * p             // -(D * w mod p) - {0, p}  (mod 2^32)
+                            : D * w.w + mulhi32(D, w.ws) * pn;          // D * w mod p + {0, p}: [0, 2p)
           }
         }
       }
