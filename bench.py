@@ -407,7 +407,7 @@ def main():
         "base_ext": n_ct * 2 * L_ * row4,
         "scale": n_ct * 3 * (L_ + k) * row4,
     }
-    profile_rows = {"ntt_fwd": "NttFwd<13, 5, 5>", "ntt_inv": "NttInv<13, 5, 2>", "relin_fused": "RelinFused",
+    profile_rows = {"ntt_fwd": "NttFwd<13, 5, 5, 0>", "ntt_inv": "NttInv<13, 5, 2>", "relin_fused": "RelinFused",
                     "scalar_mac": "Mac", "base_ext": "ExtKernelT", "scale": "ScaleKernelR"}
 
     def class_roofline(name):
@@ -417,16 +417,19 @@ def main():
         out = dict(kernel=name, avg_launch_ms=round(avg_s * 1e3, 5))
         bytes_per_launch = step_bytes[name] / per_step if name in step_bytes else None
         if name in ("ntt_fwd", "ntt_inv", "relin_fused", "tensor"):
-            # The transform is bound by integer VALU issue, not by HBM: a lazy butterfly needs 8 VALU instructions
-            # (3 multiplies, a 2-instruction conditional subtract, 3 add/sub), i.e. 8 * (n/2) * log2(n) per row =
-            # 6.5 instructions per byte moved, above the chip's balance of 39.3e12 / 8e12 = 4.9.  achieved =
-            # algorithmic instructions per launch / average launch time; `blocks` counts the transformed rows.
-            instr = kd["blocks"] / kd["launches"] * butterflies * 8
+            # The transform is bound by integer VALU issue as much as by HBM: a lazy butterfly is 7 VALU instructions
+            # on this chip (high multiplication, multiplication, multiply-add, a 2-instruction conditional subtraction,
+            # 2 additions / subtractions), i.e. 7 * (n/2) * log2(n) per row = 5.7 instructions per byte moved, above
+            # the chip's balance of 39.3e12 / 8e12 = 4.9.  achieved = algorithmic instructions per launch / average
+            # launch time; `blocks` counts the transformed rows.
+            instr = kd["blocks"] / kd["launches"] * butterflies * 7
             ach = instr / avg_s / 1e12
             out.update(bound="alu", achieved=round(ach, 2), peak=ALU_PEAK_TOPS, unit="T int32 lane-instr/s",
                        frac=round(ach / ALU_PEAK_TOPS, 4), algorithmic_instr_per_launch=int(instr))
             if ceilings:
-                out["frac_of_measured_issue_rate"] = round(ach / ceilings["mul_lo_u32_Tops"], 4)
+                # the slowest of the three multiplication forms a butterfly uses, as measured on this device
+                issue = min(ceilings[c] for c in ("mul_lo_u32_Tops", "mul_hi_u32_Tops", "mad_u64_u32_Tops"))
+                out["frac_of_measured_issue_rate"] = round(ach / issue, 4)
         else:
             out.update(bound="hbm", peak=HBM_PEAK_GBS, unit="GB/s")
             if bytes_per_launch:

@@ -108,12 +108,12 @@ HCNN_HD uint32_t bconv_prepare(const BConvDev& bc, In in, uint32_t* zcol, uint32
   uint32_t S = 0;
   for (uint32_t i = 0; i < bc.ks; ++i) {
     const Mod m = ldc(bc.src_mod, i);
-    const uint32_t z = shoup_mul(in(i), ldc(bc.zmul, i), m);
+    const uint32_t z = shoup_mul(in(i), ldc(bc.zmul, i), m.p);
     zcol[i * stride] = z;
     S += frac_est(z, m);
   }
   auto exact = [&]() {
-    for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), ldc(bc.xmul, i), ldc(bc.src_mod, i));
+    for (uint32_t i = 0; i < bc.ks; ++i) gcol[i * stride] = shoup_mul(in(i), ldc(bc.xmul, i), ldc(bc.src_mod, i).p);
     return garner_gt_half(bc, gcol, stride);
   };
   return bconv_round(S, band, exact, fallback_counter);
@@ -192,13 +192,13 @@ struct ExtKernelT {
 #pragma unroll
     for (int i = 0; i < K; ++i) {
       const Mod m = ldc(a.bc.src_mod, i);
-      z[i] = shoup_mul(x[i], ldc(a.bc.zmul, i), m);
+      z[i] = shoup_mul(x[i], ldc(a.bc.zmul, i), m.p);
       S += frac_est(z[i], m);
     }
     auto exact = [&]() {
       uint32_t* col = lds + tid;
 #pragma unroll
-      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(x[i], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i));
+      for (int i = 0; i < K; ++i) col[i * kThreads] = shoup_mul(x[i], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i).p);
       return garner_gt_half(a.bc, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact, a.fallback_counter);
@@ -306,13 +306,13 @@ struct ScaleKernelR {
 #pragma unroll
       for (int i = 0; i < K; ++i) {
         const Mod m = ldc(a.to_p.src_mod, i);
-        z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m);
+        z[i] = shoup_mul(dq[i], ldc(a.to_p.zmul, i), m.p);
         S += frac_est(z[i], m);
       }
     }
     auto exact_q = [&]() {
       for (uint32_t i = 0; i < (uint32_t)K; ++i)
-        col[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i));
+        col[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.to_p.xmul, i), ldc(a.to_p.src_mod, i).p);
       return garner_gt_half(a.to_p, col, kThreads);
     };
     const uint32_t v = bconv_round(S, a.band, exact_q, a.fallback_counter);
@@ -350,7 +350,7 @@ struct ScaleKernelR {
       }
       col[j * kThreads] = yj;                                     // made canonical by the exact path if it runs
       const Mod sm = ldc(a.to_q.src_mod, j);
-      const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm);
+      const uint32_t z2 = shoup_mul(yj, ldc(a.to_q.zmul, j), sm.p);
       S2 += frac_est(z2, sm);
       const uint32_t* b2 = a.to_q.Bp + (size_t)j * K;
 #pragma unroll
@@ -548,12 +548,15 @@ struct MacKernelDirect {
 
 // Main variant: the gather row and the F*T weights of the group are staged in LDS once per
 // workgroup (validated while staging: a bad index or weight becomes a zero-weight term on input 0;
-// the row is padded to a multiple of kMacBatch with fetches of its last input that enter no sum), so the
+// the row is padded to a multiple of kMacBatch with zero-weight terms on its last input), so the
 // term loop reads them with broadcast LDS reads and carries no data-dependent branches.  Inputs are fetched kMacBatch terms
 // ahead of their use (double buffering in registers) to keep HBM requests in flight during the
 // multiply-adds.  Requires chunk % kMacBatch == 0.
+// SKIP: the multiply-adds of the padding terms are skipped (a branch in the term loop, uniform over the workgroup).
+// Measured: 6 % faster at 8 filters x 27 terms, nothing at 5 x 25, 14 % slower at 16 filters and hundreds of
+// terms (where nothing is padded); the host picks the form by filter count and row length.
 constexpr uint32_t kMacBatch = 4;
-template <int FT>
+template <int FT, bool SKIP = false>
 struct MacKernel {
   static constexpr int kThreads = kEwThreads;
   static constexpr int kPhases = 2;
@@ -582,7 +585,8 @@ struct MacKernel {
       const int32_t* w = a.w + (size_t)g * a.F * a.T;
       for (uint32_t tau = tid; tau < Tpad + 2 * kMacBatch; tau += kThreads) {
         // the padding terms and the read-ahead slots of the last batches fetch the row's last input once more
-        // (the compute unit's cache has just seen it); they take part in no sum
+        // (the compute unit's cache has just seen it); padding terms carry weight zero, read-ahead slots are never
+        // consumed
         const bool pad = tau >= a.T;
         uint32_t src = idx[pad ? a.T - 1 : tau];
         const bool bad_src = src >= a.n_in;
@@ -621,7 +625,9 @@ struct MacKernel {
       auto consume = [&](const U4 (&buf)[kMacBatch], uint32_t t) {
 #pragma unroll
         for (uint32_t b = 0; b < kMacBatch; ++b) {
-          if (t + b >= a.T) break;              // padding terms of the last batch (uniform over the workgroup)
+          if constexpr (SKIP) {
+            if (t + b >= a.T) break;            // padding terms of the last batch
+          }
 #pragma unroll
           for (int f = 0; f < FT; ++f) {
             const int64_t wf = l_w[(size_t)f * Tpad + t + b];
@@ -746,8 +752,8 @@ struct AddSmallKernel {
     const Mod m = ldc(a.mods, l);
     const uint32_t sv = small_to_res(a.small[poly * a.n + c], m);
     uint32_t r = a.subtract_small ? sub_mod(a.x[row * a.n + c], sv, m.p) : add_mod(a.x[row * a.n + c], sv, m.p);
-    if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), ldc(a.scale, l), m), m.p);
-    if (a.msg64) r = add_mod(r, shoup_mul(reduce64(a.msg64[poly * a.n + c], m), ldc(a.scale, l), m), m.p);
+    if (a.msg) r = add_mod(r, shoup_mul(reduce32(a.msg[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
+    if (a.msg64) r = add_mod(r, shoup_mul(reduce64(a.msg64[poly * a.n + c], m), ldc(a.scale, l), m.p), m.p);
     a.out[(poly * a.out_poly_rows + a.out_row0 + l) * a.n + c] = r;
   }
 };
@@ -971,7 +977,7 @@ struct NoiseKernel {
     uint32_t* dig = lds + tid;                                   // mixed-radix digits
     uint32_t* word = lds + (size_t)ks * kThreads + tid;          // multiword |r|, least significant first
     for (uint32_t i = 0; i < ks; ++i)
-      dig[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i));
+      dig[i * kThreads] = shoup_mul(src[(size_t)i * n], ldc(a.bc.xmul, i), ldc(a.bc.src_mod, i).p);
     if (garner_gt_half(a.bc, dig, kThreads)) {
       // digits of q - R: zero while the lower digits of R are zero, q_i - d_i at the first non-zero digit,
       // q_i - 1 - d_i above it

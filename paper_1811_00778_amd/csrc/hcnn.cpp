@@ -127,8 +127,6 @@ Mod h_mod(uint32_t p) {
   m.c32 = (uint32_t)((1ull << 32) % p);
   m.c32s = (uint32_t)(((uint64_t)m.c32 << 32) / p);
   m.mu = (uint32_t)((1ull << 61) / p);
-  m.pn = 0u - p;
-  m.pad[0] = m.pad[1] = m.pad[2] = 0;
   return m;
 }
 
@@ -336,7 +334,7 @@ template <> struct KernelClass<ScaleKernel> { static constexpr int id = HCNN_PRO
 template <int A> struct KernelClass<RelinMacKernel<A>> { static constexpr int id = HCNN_PROF_RELIN_MAC; };
 template <int A, int B, int C> struct KernelClass<RelinFused<A, B, C>> { static constexpr int id = HCNN_PROF_RELIN_FUSED; };
 template <int A, int B> struct KernelClass<TensorFused<A, B>> { static constexpr int id = HCNN_PROF_TENSOR; };
-template <int F> struct KernelClass<MacKernel<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
+template <int F, bool S> struct KernelClass<MacKernel<F, S>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 template <int F> struct KernelClass<MacKernelDirect<F>> { static constexpr int id = HCNN_PROF_SCALAR_MAC; };
 
 int take_event(hcnn_ctx* c, hcnn_event_t* ev) {
@@ -491,8 +489,9 @@ int build_tables(hcnn_ctx* c) {
     nl.ninv_r = h_shoup(ninv_r, p);
     nl.w1ninv_r = h_shoup(h_mulmod(twi[(size_t)l * n + 1].w, ninv_r, p), p);
     nl.pinv = h_neg_inv32(p);
+    nl.pneg = 0u - p;
     nl.zero = 0;
-    nl.pad[0] = nl.pad[1] = 0;
+    nl.pad = 0;
     mods.push_back(nl.m);
     limbs.push_back(nl);
   }
@@ -674,6 +673,8 @@ int mac_launch(hcnn_ctx* c, size_t grid, const MacArgs& a) {
     // At most four workgroups per compute unit (requested through the LDS size): the inputs that the resident
     // workgroups of a die gather from then stay within its L2 (measured: 5-10 % faster on convolution shapes).
     const size_t lds_req = std::max<size_t>(lds, 36 * 1024);
+    if (FT <= 8 && a.T % kMacBatch != 0)        // padded rows at few filters: skip the padding terms' multiply-adds
+      return run<MacKernel<FT, true>>(c, MacKernel<FT>::grid(tiles, a.G), lds_req, b);
     return run<MacKernel<FT>>(c, MacKernel<FT>::grid(tiles, a.G), lds_req, b);
   }
   return run<MacKernelDirect<FT>>(c, grid, 0, a);

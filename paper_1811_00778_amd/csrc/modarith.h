@@ -6,17 +6,12 @@
 
 namespace hcnn {
 
-// Per-prime constants (32 bytes).
+// Per-prime constants (16 bytes).
 struct Mod {
   uint32_t p;     // the prime
   uint32_t c32;   // 2^32 mod p
   uint32_t c32s;  // floor(c32 * 2^32 / p)
   uint32_t mu;    // floor(2^61 / p)  (fits 32 bits because p > 2^29)
-  // -p mod 2^32.  The reductions subtract multiples of p; written as sums with this word they compile to chains of
-  // multiply-adds (one instruction per term), where a visible subtraction of q*p costs a multiplication and a
-  // subtraction.  It must come from memory: the compiler turns a negation it can see back into the subtraction.
-  uint32_t pn;
-  uint32_t pad[3];
 };
 
 // A constant w < p with its Shoup companion floor(w * 2^32 / p).
@@ -32,36 +27,36 @@ HCNN_HD uint32_t mulhi32(uint32_t a, uint32_t b) {
 #endif
 }
 
+// x * w mod p up to one extra p: result in [0, 2p) for ANY x < 2^32.
+HCNN_HD uint32_t shoup_lazy(uint32_t x, uint32_t w, uint32_t ws, uint32_t p) {
+  uint32_t q = mulhi32(x, ws);
+  return x * w - q * p;
+}
+
 HCNN_HD uint32_t csub(uint32_t x, uint32_t p) { return x >= p ? x - p : x; }
 
 // x * w mod p, canonical.
-HCNN_HD uint32_t shoup_mul(uint32_t x, ShoupConst c, const Mod& m) {
-  return csub(x * c.w + mulhi32(x, c.ws) * m.pn, m.p);
-}
-
-// x mod p for any x < 2^64, canonical.
-// x mod p up to three extra p: result in [0, 4p) for any x < 2^64.
-//   hi * 2^32 mod p, in [0, 2p)  =  hi * c32 - floor(hi * c32s / 2^32) * p      (Shoup)
-//   lo mod p,        in [0, 2p)  =  lo - qb * p,  qb = floor(lo / p) or one less (Barrett)
-// summed in one chain of multiply-adds (mod 2^32; the true sum is below 4p < 2^32).
-HCNN_HD uint32_t reduce64_lazy(uint64_t x, const Mod& m) {
-  const uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
-  const uint32_t qa = mulhi32(hi, m.c32s);
-  const uint32_t qb = mulhi32(lo, m.mu) >> 29;
-  uint32_t s = hi * m.c32 + lo;
-  s = qa * m.pn + s;
-  s = qb * m.pn + s;
-  return s;
+HCNN_HD uint32_t shoup_mul(uint32_t x, ShoupConst c, uint32_t p) {
+  return csub(shoup_lazy(x, c.w, c.ws, p), p);
 }
 
 // x mod p for any x < 2^64, canonical.
 HCNN_HD uint32_t reduce64(uint64_t x, const Mod& m) {
-  return csub(csub(reduce64_lazy(x, m), 2 * m.p), m.p);
+  uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
+  uint32_t y = shoup_lazy(hi, m.c32, m.c32s, m.p);        // hi * 2^32 mod p, in [0, 2p)
+  uint32_t qb = mulhi32(lo, m.mu) >> 29;                  // floor(lo/p) or one less
+  uint32_t b = lo - qb * m.p;                             // in [0, 2p)
+  uint32_t s = y + b;                                     // < 4p < 2^32
+  s = csub(s, 2 * m.p);
+  return csub(s, m.p);
 }
 
 // x mod p up to one extra p: result in [0, 2p) for any x < 2^64.
 HCNN_HD uint32_t reduce64_2p(uint64_t x, const Mod& m) {
-  return csub(reduce64_lazy(x, m), 2 * m.p);
+  uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
+  uint32_t y = shoup_lazy(hi, m.c32, m.c32s, m.p);
+  uint32_t qb = mulhi32(lo, m.mu) >> 29;
+  return csub(y + (lo - qb * m.p), 2 * m.p);
 }
 
 // Montgomery reduction: x * 2^-32 mod p up to one extra p, for x < p * 2^32 (in particular for the
@@ -74,7 +69,7 @@ HCNN_HD uint32_t redc_2p(uint64_t x, uint32_t p, uint32_t pinv) {
 // x mod p for x < 2^32, canonical.
 HCNN_HD uint32_t reduce32(uint32_t x, const Mod& m) {
   uint32_t qb = mulhi32(x, m.mu) >> 29;
-  return csub(qb * m.pn + x, m.p);
+  return csub(x - qb * m.p, m.p);
 }
 
 // x * 2^-32 mod p, canonical, for any x < 3 * 2^62: a Montgomery step (result below 2^32) followed by a
@@ -91,6 +86,14 @@ HCNN_HD uint32_t mont_step(uint64_t x, uint32_t p, uint32_t pinv) {
 }
 // such a sum may hold kMontRoom products of two values below 2^30 (11 * 2^60 plus small terms < 3 * 2^62)
 constexpr uint32_t kMontRoom = 11;
+
+// x mod p up to three extra p: result in [0, 4p) for any x < 2^64.
+HCNN_HD uint32_t reduce64_lazy(uint64_t x, const Mod& m) {
+  uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
+  uint32_t y = shoup_lazy(hi, m.c32, m.c32s, m.p);
+  uint32_t qb = mulhi32(lo, m.mu) >> 29;
+  return y + (lo - qb * m.p);
+}
 
 HCNN_HD uint32_t mul_mod(uint32_t a, uint32_t b, const Mod& m) { return reduce64((uint64_t)a * b, m); }
 

@@ -29,8 +29,12 @@ struct NttLimb {
   ShoupConst ninv_r;    // n^-1 * 2^32 mod p
   ShoupConst w1ninv_r;  // (inverse twiddle of node 1) * n^-1 * 2^32 mod p
   uint32_t pinv;        // -p^-1 mod 2^32
+  uint32_t pneg;        // -p mod 2^32.  The compiler folds a 32-bit product into a following addition (one multiply-add)
+                        // but not into a subtraction: written x*w + q*pneg, the lazy product x*w - q*p is a
+                        // multiplication and a multiply-add.  The word has to come from memory for that: a negation
+                        // the compiler can see is turned back into the subtraction.
   uint32_t zero;        // 0, unknown to the compiler: zero - w is the negated twiddle and stays one (see the inverse butterfly)
-  uint32_t pad[2];
+  uint32_t pad;
 };
 
 // Row r (= workgroup index) belongs to group r / limb_cycle and limb limb_base + r % limb_cycle.
@@ -477,7 +481,7 @@ struct NttInv {
         }
       }
       const uint32_t root = (1u << S0) + i;
-      const uint32_t pn = L.m.pn;
+      const uint32_t pn = L.pneg;
 #pragma unroll
       for (int l = NS - 1; l >= 0; --l) {
         const int half = NET >> (l + 1);
