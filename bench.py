@@ -89,11 +89,13 @@ def time_layer(cid, torch, binding, layers, gen, reps=3, relin_order=0, square=T
     ct_bytes = 2 * k * n * 4
     mac = sorted(mac_ms)[len(mac_ms) // 2]
     sq = sorted(sq_ms)[len(sq_ms) // 2]
-    return dict(n=n, k=k, inputs=n_in, outputs=F * G, terms=int(idx_h.shape[1]),
-                mac_ms=round(mac, 4), square_relin_ms=round(sq, 4), layer_ms=round(mac + sq, 4),
-                mac_compulsory_GBps=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9, 1),
-                mac_hbm_frac=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                squarings=int(flat.shape[0]), squarings_per_s=round(flat.shape[0] / (sq * 1e-3), 1))
+    out = dict(n=n, k=k, inputs=n_in, outputs=F * G, terms=int(idx_h.shape[1]), mac_ms=round(mac, 4),
+               mac_compulsory_GBps=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9, 1),
+               mac_hbm_frac=round((n_in + F * G) * ct_bytes / (mac * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+    if square:
+        out.update(square_relin_ms=round(sq, 4), layer_ms=round(mac + sq, 4),
+                   squarings=int(flat.shape[0]), squarings_per_s=round(flat.shape[0] / (sq * 1e-3), 1))
+    return out
 
 
 def run_only(args, torch, binding, layers, gen):
