@@ -643,12 +643,16 @@ int ntt_dense(hcnn_ctx* c, const uint32_t* in, uint32_t* out, size_t rows, uint3
 }
 
 // Base-conversion kernels: register-resident variants for the basis sizes of the standard
-// parameter sets, the generic LDS-column kernels otherwise.
+// parameter sets, the generic LDS-column kernels otherwise (about four times slower in the scaling step).
+// k' = k + 1 covers t = 65537 up to n = 8192, k' = k + 2 the larger rings and the larger plaintext moduli.
+#define HCNN_REGISTER_BASES(X)                                                                          \
+  X(2, 3) X(3, 4) X(4, 5) X(5, 6) X(6, 7) X(7, 8) X(8, 9) X(9, 10) X(10, 11) X(11, 12) X(12, 13)        \
+  X(4, 6) X(6, 8) X(8, 10) X(10, 12) X(11, 13) X(12, 14) X(14, 16) X(16, 18) X(24, 26)
 int ext_dispatch(hcnn_ctx* c, size_t grid, const ExtArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_EXT_CASE(K, KP) \
   if (k == K && kp == KP) return run<ExtKernelT<K, KP>>(c, grid, ExtKernelT<K, KP>::lds_bytes(), a);
-  HCNN_EXT_CASE(2, 3) HCNN_EXT_CASE(4, 5) HCNN_EXT_CASE(8, 9) HCNN_EXT_CASE(10, 12) HCNN_EXT_CASE(11, 12) HCNN_EXT_CASE(11, 13) HCNN_EXT_CASE(12, 13) HCNN_EXT_CASE(12, 14) HCNN_EXT_CASE(16, 18) HCNN_EXT_CASE(24, 26)
+  HCNN_REGISTER_BASES(HCNN_EXT_CASE)
 #undef HCNN_EXT_CASE
   return run<ExtKernel>(c, grid, ExtKernel::lds_bytes(k), a);
 }
@@ -657,7 +661,7 @@ int scale_dispatch(hcnn_ctx* c, size_t grid, const ScaleArgs& a) {
   const uint32_t k = c->k, kp = c->kp;
 #define HCNN_SCALE_CASE(K, KP) \
   if (k == K && kp == KP) return run<ScaleKernelR<K, KP>>(c, grid, ScaleKernelR<K, KP>::lds_bytes(), a);
-  HCNN_SCALE_CASE(2, 3) HCNN_SCALE_CASE(4, 5) HCNN_SCALE_CASE(8, 9) HCNN_SCALE_CASE(10, 12) HCNN_SCALE_CASE(11, 12) HCNN_SCALE_CASE(11, 13) HCNN_SCALE_CASE(12, 13) HCNN_SCALE_CASE(12, 14) HCNN_SCALE_CASE(16, 18) HCNN_SCALE_CASE(24, 26)
+  HCNN_REGISTER_BASES(HCNN_SCALE_CASE)
 #undef HCNN_SCALE_CASE
   return run<ScaleKernel>(c, grid, ScaleKernel::lds_bytes(k, kp), a);
 }

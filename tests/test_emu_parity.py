@@ -121,8 +121,10 @@ def test_square_relin_more_than_16_limbs(backend):
     pc.check_square_relin(backend, 1024, 17, n_random=1, n_genuine=1)
 
 
-@pytest.mark.parametrize("k,k_aux,big_t", [(8, 9, False), (11, 12, False), (12, 13, False), (10, 12, True), (11, 13, True),
-                                           (12, 14, True), (16, 18, True), (24, 26, True)])
+@pytest.mark.parametrize("k,k_aux,big_t", [(3, 4, False), (5, 6, False), (6, 7, False), (7, 8, False), (8, 9, False),
+                                           (9, 10, False), (10, 11, False), (11, 12, False), (12, 13, False),
+                                           (4, 6, True), (6, 8, True), (8, 10, True), (10, 12, True), (11, 13, True),
+                                           (12, 14, True), (14, 16, True), (16, 18, True), (24, 26, True)])
 def test_square_relin_register_variants_of_standard_bases(backend, k, k_aux, big_t):
     # the basis sizes of the benchmark configurations, at a ring degree the oracle finishes quickly;
     # a larger plaintext modulus makes k' = k + 2 necessary already at n = 1024
