@@ -141,6 +141,31 @@ struct NttGeom {
   static constexpr int ns(int ph) { return ph < kPhases - 1 ? LOGR : LOGN - LOGR * (kPhases - 1); }
 };
 
+// n = 32768: four passes of 5 + 4 + 4 + 2 stages.  The last forward pass (the first inverse one) has every thread store
+// (load) 2^ns consecutive residues; with five stages there that is 128 bytes per lane, one cache line per lane and
+// access, eight times the line accesses the bytes need.  Two stages there make it one 16-byte word per lane: the lanes of
+// a wave touch consecutive words.  Measured against 5 + 5 + 5: whole-row forward 119 -> 98 ns per row, the inverse
+// transforms of a squaring 123 -> 103, although the row makes one more trip through the LDS (5 + 5 + 3 + 2 and
+// 4 + 5 + 4 + 2 are within 2 % of it; 5 + 5 + 4 + 1, eight bytes per lane, gains nothing).  The half-row network of
+// that ring's two-workgroup forward transform (14 stages, 32 residues per thread) takes 5 + 4 + 3 + 2 for the same
+// reason (2 % faster than 5 + 5 + 4).  At n = 8192 the three passes 5 + 5 + 3 (32 bytes per lane) stay: 5 + 4 + 2 + 2,
+// 5 + 3 + 3 + 2 and 5 + 4 + 4 were each 3-5 % slower.
+#define HCNN_GEOM_SPEC(LOGN_, LOGR_, NP_, ...)                                                        \
+  template <>                                                                                          \
+  struct NttGeom<LOGN_, LOGR_> {                                                                       \
+    static constexpr int N = 1 << LOGN_;                                                               \
+    static constexpr int R = 1 << LOGR_;                                                               \
+    static constexpr int kThreads = N / R;                                                             \
+    static constexpr int kPhases = NP_;                                                                \
+    static constexpr size_t kLdsBytes = (size_t)(N + N / 32) * 4;                                      \
+    static constexpr int kNs[NP_] = {__VA_ARGS__};                                                     \
+    static constexpr int s0(int ph) { int s = 0; for (int i = 0; i < ph; ++i) s += kNs[i]; return s; } \
+    static constexpr int ns(int ph) { return kNs[ph]; }                                                \
+  };
+HCNN_GEOM_SPEC(15, 5, 4, 5, 4, 4, 2)
+HCNN_GEOM_SPEC(14, 5, 4, 5, 4, 3, 2)
+#undef HCNN_GEOM_SPEC
+
 // ------------------------------------------------------------------------- forward
 // SPLIT = 1: two workgroups per row.  The first stage of the forward transform pairs element i with element
 // i + n/2 and leaves two halves that never meet again; workgroup (row, half) computes its half of that stage while
