@@ -1401,7 +1401,8 @@ int hcnn_measure_ceiling(hcnn_ctx* c, int which, double* value_out) {
     dev_free(src);
     dev_free(dst);
     if (e || es) return e ? e : es;
-    *value_out = (which == HCNN_CEIL_COPY ? 2.0 : 1.0) * (double)bytes / (ms * 1e-3) / 1e9;
+    // (a build that does not time its launches -- the host emulation -- reports 0)
+    *value_out = ms > 0.0 ? (which == HCNN_CEIL_COPY ? 2.0 : 1.0) * (double)bytes / (ms * 1e-3) / 1e9 : 0.0;
     return HCNN_OK;
   }
   void* out = nullptr;
@@ -1418,7 +1419,7 @@ int hcnn_measure_ceiling(hcnn_ctx* c, int which, double* value_out) {
   }
   dev_free(out);
   if (e) return e;
-  *value_out = (double)grid * kRateThreads * kRateIters * kRateChains / (ms * 1e-3) / 1e12;
+  *value_out = ms > 0.0 ? (double)grid * kRateThreads * kRateIters * kRateChains / (ms * 1e-3) / 1e12 : 0.0;
   return HCNN_OK;
 }
 

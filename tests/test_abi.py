@@ -126,3 +126,5 @@ def test_set_option_validation_needs_no_device(lib):
     assert lib.hcnn_set_option(None, _capi.OPT_PROFILE, 1) == _capi.ERR["NULL"]
     assert lib.hcnn_get_stat(None, 0, None) == _capi.ERR["NULL"]
     assert lib.hcnn_profile_read(None, 0, None, None, None) == _capi.ERR["NULL"]
+    assert lib.hcnn_measure_ceiling(None, 0, None) == _capi.ERR["NULL"]
+    assert lib.hcnn_ct_square_relin_noalloc(None, None, 1, None) == _capi.ERR["NULL"]

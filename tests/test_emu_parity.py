@@ -146,6 +146,20 @@ def test_square_relin_largest_ring_two_workgroups_per_forward_row(backend):
     pc.check_square_relin(backend, 32768, 2, n_random=2, n_genuine=0)
 
 
+def test_measure_ceiling_arguments(backend):
+    # the diagnostic rejects an unknown probe; the host emulation does not time its launches and reports 0
+    from paper_1811_00778_amd import _capi
+    import ctypes
+    s = pc.Setup(backend, 1024, 2, with_keys=False)
+    v = ctypes.c_double(-1.0)
+    lib = s.ctx.raw.lib
+    assert lib.hcnn_measure_ceiling(s.ctx.raw.handle, len(_capi.CEILINGS), ctypes.byref(v)) == _capi.ERR["ARG"]
+    assert lib.hcnn_measure_ceiling(s.ctx.raw.handle, -1, ctypes.byref(v)) == _capi.ERR["ARG"]
+    assert lib.hcnn_measure_ceiling(s.ctx.raw.handle, 0, None) == _capi.ERR["NULL"]
+    assert lib.hcnn_measure_ceiling(s.ctx.raw.handle, len(_capi.CEILINGS) - 1, ctypes.byref(v)) == 0 and v.value == 0.0
+    s.ctx.close()
+
+
 def test_general_hmult(backend):
     pc.check_mul_relin(backend, 1024, 2)
     pc.check_mul_relin(backend, 2048, 3, force_exact=True)

@@ -301,6 +301,20 @@ def test_options_and_profile(backend):
     ctx.close()
 
 
+def test_measured_ceilings_are_plausible(backend):
+    """The diagnostic entry point behind the bench line's `measured_ceilings`: streaming rates below the 8 TB/s of the
+    memory and above a tenth of it, instruction-issue rates between a quarter of and twice 256 CU x 64 lanes x 2.4 GHz."""
+    from paper_1811_00778_amd import _capi
+    s = pc.Setup(backend, 1024, 2, with_keys=False)
+    c = s.ctx.measured_ceilings()
+    assert set(c) == set(_capi.CEILINGS)
+    for name in ("copy_GBps", "read_GBps", "write_GBps"):
+        assert 800.0 < c[name] < 8000.0, (name, c[name])
+    for name in ("mul_lo_u32_Tops", "mul_hi_u32_Tops", "mad_u64_u32_Tops", "mad_i64_i32_Tops", "add_u32_Tops"):
+        assert 9.8 < c[name] < 2 * 39.4, (name, c[name])
+    s.ctx.close()
+
+
 def test_empty_batches_are_noops(backend):
     s = pc.Setup(backend, 1024, 2)
     ctx = s.ctx
