@@ -1077,7 +1077,10 @@ static int mul_relin_impl(hcnn_ctx* c, const uint32_t* in, const uint32_t* in_b,
         case 10: e = HCNN_FUSED(10, 4); break;
         case 11: e = HCNN_FUSED(11, 4); break;
         case 12: e = HCNN_FUSED(12, 4); break;
-        case 13: e = HCNN_FUSED(13, 5); break;
+        // n = 8192: 32 residues per thread (three passes, 8 waves per compute unit) when the launch holds several
+        // rounds of workgroups; a single round runs 5 % shorter at 16 residues per thread (four passes, 16 waves per
+        // compute unit hide more of what no other round overlaps).  Both forms hold two workgroups per compute unit.
+        case 13: e = nf > std::max<size_t>(fused_round, 1) ? HCNN_FUSED(13, 5) : HCNN_FUSED(13, 4); break;
         case 14: e = HCNN_FUSED(14, 4); break;
         default: e = HCNN_ERR_N; break;
       }

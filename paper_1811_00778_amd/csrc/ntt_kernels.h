@@ -164,6 +164,7 @@ struct NttGeom {
   };
 HCNN_GEOM_SPEC(15, 5, 4, 5, 4, 4, 2)
 HCNN_GEOM_SPEC(14, 5, 4, 5, 4, 3, 2)
+HCNN_GEOM_SPEC(13, 4, 4, 4, 3, 4, 2)
 #undef HCNN_GEOM_SPEC
 
 // ------------------------------------------------------------------------- forward

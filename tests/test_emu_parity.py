@@ -138,6 +138,8 @@ def test_square_relin_at_a_degree_with_die_aware_block_orders(backend):
     # workgroups by accelerator die; three ciphertexts so that the ciphertext index is exercised too
     pc.check_square_relin(backend, 8192, 2, n_random=3, n_genuine=0)
     pc.check_square_relin(backend, 8192, 2, n_random=6, n_genuine=0, relin_order=2)    # key-major order forced
+    # one ciphertext: the forced one-kernel relinearisation takes its single-round form (16 residues per thread)
+    pc.check_square_relin(backend, 8192, 2, n_random=1, n_genuine=0)
 
 
 def test_square_relin_largest_ring_two_workgroups_per_forward_row(backend):
