@@ -31,7 +31,8 @@ class _Backend:
 
 
 @pytest.mark.parametrize("n,k,first,second", [(4096, 4, 40, 7),      # one internal batch each
-                                              (8192, 8, 30, 3)])     # 30 ciphertexts exceed the array: two internal batches
+                                              (8192, 8, 30, 3),      # 30 ciphertexts exceed the array: two internal batches
+                                              (32768, 2, 5, 2)])     # the largest ring stages its extended rows in the tensor's array
 def test_noalloc_equals_allocating_entry_point(n, k, first, second):
     import torch
     print("[no-alloc] n=%d k=%d, %d then %d ciphertexts" % (n, k, first, second), flush=True)
