@@ -356,6 +356,9 @@ struct NttInv {
   using G = NttGeom<LOGN, LOGR>;
   static constexpr int kThreads = G::kThreads;
   static constexpr int kPhases = G::kPhases;
+  // a 1024-thread workgroup whose row leaves LDS for a second one: keep the registers within what two of them need
+  // (the plain transform of n = 16384 took 68 and ran alone on its compute unit, a third slower per row)
+  static constexpr int kMinWavesPerSimd = (G::kThreads == 1024 && 2 * G::kLdsBytes <= 160 * 1024) ? 8 : 1;
   static constexpr bool kFromRegs = IO == kNttFromRegs0 || IO == kNttFromRegs1;
   static constexpr bool kTensorRegs = IO == kNttTensorRegs0 || IO == kNttTensorRegs1 || IO == kNttTensorRegs2;
   using Regs = std::conditional_t<kFromRegs, RelinRegs<G::R>, std::conditional_t<kTensorRegs, TensorRegs<G::R>, NoRegs>>;
