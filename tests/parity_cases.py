@@ -134,6 +134,13 @@ def check_scalar_mac(backend, n, k, seed_id=1):
     w40 = gen.int_weights(s.rng, (2, 3, 41), mid)
     w40[1, 2, :] = -mid
     run(idx40, w40, mid)
+    # rows of 27 and 9 terms (padded by one and by three terms; at up to 8 filters the form that skips the padding
+    # terms' multiply-adds), with partial sums reduced every 4 terms and with small weights
+    idx27 = s.rng.integers(0, n_in, size=(2, 27)).astype(np.uint32)
+    w27 = gen.int_weights(s.rng, (2, 8, 27), mid)
+    w27[0, 7, :] = mid
+    run(idx27, w27, mid)
+    run(idx27[:, :9].copy(), gen.int_weights(s.rng, (2, 3, 9), 7), 7)
     # a gather row too long for the LDS-staged kernel takes the direct variant ((1+F)*T*4 > 64 KiB)
     long_idx = s.rng.integers(0, n_in, size=(1, 5000)).astype(np.uint32)
     run(long_idx, gen.int_weights(s.rng, (1, 3, 5000), 100), 100)
