@@ -153,16 +153,15 @@ def _main(argv=None):
     t = args.t or (65537 if args.name == "mnist" else 2424833)
     q, p = binding.choose_moduli(args.n, k, t)
     ctx = binding.Context(args.n, q, p, t)
-    gen = torch.Generator(device=ctx.device)
-    gen.manual_seed(1811)
-    rnd = lambda *shape: torch.randint(0, 1 << 29, shape, dtype=torch.int32, device=ctx.device, generator=gen)
-    ctx.set_relin_key(rnd(k, 2, k, args.n))
+    # uniformly random canonical residues (below each q_l), drawn on the device by the library's sampler
+    ctx.set_relin_key(ctx.sample_uniform(1811, 2, k * 2).reshape((k, 2, k, args.n)))
     rng = np.random.default_rng(1811)
     bound = 15 if args.name == "mnist" else 7
     weights = [None if s is None else rng.integers(-bound, bound + 1, size=s).astype(np.int32)
                for s in weight_shapes(spec, in_shape)]
     plan = Plan(spec, in_shape, weights, ctx.to_device)
-    cts = rnd(in_shape[0] * in_shape[1] * in_shape[2], 2, k, args.n)
+    n_in = in_shape[0] * in_shape[1] * in_shape[2]
+    cts = ctx.sample_uniform(1811, 1, n_in * 2).reshape((n_in, 2, k, args.n))
     n_mul, n_sq = op_counts(spec, in_shape)
     for r in range(args.reps + 1):
         torch.cuda.synchronize()
